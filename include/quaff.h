@@ -1,0 +1,169 @@
+/*
+ * quaff.h - C ABI of the MI355X (gfx950) implementation of the Quaff quantized linear layer
+ * (arXiv 2505.14742, Sec. 3 "Methodology").
+ *
+ * One fine-tuning step of one linear layer Y = X W (X [t x c_in] tokens x input channels,
+ * W [c_in x c_out], Sec. 2.2) runs as
+ *
+ *     quaff_scale_update   momentum scales on the fixed outlier channels O        (Eq. 7, Eq. 8)
+ *                          and the dynamic outlier weights what = (s_O - 1) W_O   (Eq. 5, Eq. 9)
+ *     quaff_quant_act      Xhat = X s^-1 on the O columns, per-token INT8 codes   (Eq. 5, Eq. 1)
+ *     quaff_linear_fwd     Y = Dx (Xq Wq Dw + xq_O what_int Dwhat) + LoRA branch  (Eq. 9; App. "settings")
+ *     quaff_linear_bwd_dx  dX = dY W^T through the same INT8 product + LoRA branch
+ *
+ * preceded once per layer by quaff_prepare_weight (Sec. 3.3: quantize the frozen W, keep W_O).
+ *
+ * Conventions
+ *  - Every data pointer is a DEVICE pointer owned by the caller, valid on the device that is current when
+ *    the call is made; the library never frees or keeps them.  Except where stated the library allocates
+ *    nothing: scratch comes from the caller's `workspace` (quaff_workspace_bytes tells how much).
+ *  - All work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the default stream) and the
+ *    call returns without synchronizing.  Nothing is printed.
+ *  - Matrices are row-major.  bf16 values are passed as uint16_t bit patterns.
+ *  - c_in and c_out must be multiples of 16; t >= 1; n_outlier >= 0; lora_rank is 0 or a multiple of 16
+ *    (at most 128).  Data pointers must be 16-byte aligned and leading dimensions multiples of 8 elements.
+ *  - O must be sorted, unique and inside [0, c_in): a documented precondition, not checked on the device.
+ *    Non-finite inputs are outside the contract (no hang, no out-of-bounds access, values unspecified).
+ *  - Return value: QUAFF_OK or a negative QUAFF_ERR_* code; nothing has been enqueued when an error is
+ *    returned for an argument problem.
+ *  - n_p ("padded outlier count") is n_outlier rounded up to a multiple of 64 (0 stays 0); see
+ *    quaff_padded_outliers.
+ *
+ * Arithmetic contract.  Integer codes and int32 accumulators are exact.  Quantization decisions are taken
+ * in IEEE fp32, one rounding per operation, ties to even: for a group (token row / output channel) with
+ * absolute maximum m, the step is Delta = m / 127, codes are rne(x * (127 / m)) clamped to [-127, 127], and
+ * a group with m = 0 gets Delta = 0 and all-zero codes.  Dequantised outputs are computed in fp32.
+ */
+#ifndef QUAFF_H_
+#define QUAFF_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define QUAFF_OK 0
+#define QUAFF_ERR_NULL (-1)      /* a required pointer is NULL */
+#define QUAFF_ERR_SHAPE (-2)     /* a size is out of the supported range */
+#define QUAFF_ERR_WORKSPACE (-3) /* workspace missing or too small */
+#define QUAFF_ERR_ALIGN (-4)     /* a pointer or leading dimension is misaligned */
+#define QUAFF_ERR_HIP (-5)       /* a HIP call failed; see quaff_last_hip_error */
+
+/* Human-readable name of a status code (static string, never NULL). */
+const char* quaff_status_string(int status);
+
+/* hipError_t value of the last failed HIP call made by this library on the calling thread (0 if none). */
+int quaff_last_hip_error(void);
+
+/* n_p: n_outlier rounded up to the INT8 MFMA contraction step (64). */
+int32_t quaff_padded_outliers(int32_t n_outlier);
+
+/* Bytes of the opaque packed INT8 weight produced by quaff_prepare_weight.  The packing stores the codes
+ * contraction-contiguous for both products of the layer (over c_in for Y, over c_out for dX). */
+size_t quaff_packed_weight_bytes(int64_t c_in, int64_t c_out);
+
+/* Bytes of scratch that the per-step calls below need for the given problem (the maximum over the calls). */
+size_t quaff_workspace_bytes(int64_t t, int64_t c_in, int64_t c_out, int32_t n_outlier, int32_t lora_rank);
+
+/*
+ * Offline weight preprocessing (Sec. 3.3, "weights preprocessing"): per-output-channel Eq. 1 on the frozen
+ * full-precision W, retaining the outlier rows W_O in full precision.
+ *   in : W [c_in x c_out] fp32, leading dimension ldw;  O [n_outlier] int32 (may be NULL when n_outlier = 0)
+ *   out: Wq_packed  opaque, quaff_packed_weight_bytes(c_in, c_out) bytes
+ *        delta_w    [c_out] fp32 step sizes
+ *        W_O        [n_outlier x c_out] fp32 copy of the O rows of W       (may be NULL when n_outlier = 0)
+ *        wmax_O     [n_outlier] fp32, max_j |W_O[k, j]| (the max|W_i| of Eq. 8) (may be NULL when n_outlier = 0)
+ *        Wq_plain   optional [c_in x c_out] int8 codes in the paper's layout (NULL to skip)
+ * `workspace` must hold at least 4 * c_out * ceil(c_in / 64) bytes... see quaff_prepare_workspace_bytes.
+ */
+size_t quaff_prepare_workspace_bytes(int64_t c_in, int64_t c_out);
+int quaff_prepare_weight(const float* W, int64_t c_in, int64_t c_out, int64_t ldw, const int32_t* O,
+                         int32_t n_outlier, void* Wq_packed, float* delta_w, float* W_O, float* wmax_O,
+                         int8_t* Wq_plain, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Targeted momentum scaling (Eq. 7, Eq. 8) and the dynamic outlier weights (Eq. 5, quantized as in Eq. 9).
+ *   cmax_k = max_i |X[i, O_k]| over all t tokens of the unscaled X
+ *   beta_k = max(1, sqrt(cmax_k / wmax_k))   (1 when wmax_k = 0)
+ *   s_k    = gamma * s_k + (1 - gamma) * beta_k
+ *   what[k, j] = (s_k - 1) * W_O[k, j], quantized per output channel j -> what_int, delta_what
+ *   in    : X [t x c_in] bf16 (ldx); O, W_O, wmax_O as produced by quaff_prepare_weight; gamma in [0, 1]
+ *   in/out: s_O [n_outlier] fp32 - the only state carried from step to step
+ *   out   : colscale [c_in] fp32: entries O_k are overwritten with 1 / s_k; all other entries are left
+ *           untouched (the caller initialises the array to 1.0f once)
+ *           what_int [c_out x n_p] int8, row j holds the codes of output channel j for k = 0..n_outlier-1,
+ *           zero for k >= n_outlier;  delta_what [c_out] fp32
+ *           cmax_out [n_outlier] fp32, optional (NULL to skip)
+ * With n_outlier = 0 the call is a no-op that returns QUAFF_OK.
+ */
+int quaff_scale_update(const uint16_t* X, int64_t t, int64_t c_in, int64_t ldx, const int32_t* O,
+                       int32_t n_outlier, const float* W_O, const float* wmax_O, int64_t c_out, float gamma,
+                       float* s_O, float* colscale, int8_t* what_int, float* delta_what, float* cmax_out,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Column scaling and per-token quantization (Eq. 5 then Eq. 1 with one step size per token,
+ * App. "Quantization Granularity").
+ *   xhat[i, j] = X[i, j] * colscale[j]           (colscale NULL = all ones)
+ *   delta[i]   = max_j |xhat[i, j]| / 127,  Xq[i, j] = rne(xhat[i, j] * (127 / max_j |xhat[i, j]|))
+ *   xq_O[i, k] = Xq[i, O_k]  (the shared activation codes of Eq. 9's remark), zero for k >= n_outlier
+ *   in : X [t x c] bf16 (ldx);  colscale [c] fp32 or NULL;  O [n_outlier] or NULL
+ *   out: Xq [t x c] int8 (dense, leading dimension c);  delta [t] fp32;
+ *        xq_O [t x n_p] int8 (NULL to skip; required layout for quaff_linear_fwd)
+ * Used for X in the forward pass and, with colscale = delta_w, for dY in the backward pass.
+ */
+int quaff_quant_act(const uint16_t* X, int64_t t, int64_t c, int64_t ldx, const float* colscale,
+                    const int32_t* O, int32_t n_outlier, int8_t* Xq, float* delta, int8_t* xq_O, void* stream);
+
+/*
+ * Integer forward with dequantising epilogue (Eq. 9) and the LoRA branch (rank r, App. "Model and
+ * experimental settings"; no dropout):
+ *   acc1 = Xq Wq,  acc2 = xq_O what_int                                   (int32, exact)
+ *   Y[i, j] = delta_x[i] * (acc1[i, j] * delta_w[j] + acc2[i, j] * delta_what[j])
+ *           + lora_scale * sum_p (sum_k X[i, k] A[k, p]) B[p, j]
+ *   in : Xq [t x c_in], delta_x [t], xq_O [t x n_p] from quaff_quant_act; Wq_packed, delta_w from
+ *        quaff_prepare_weight; what_int [c_out x n_p], delta_what [c_out] from quaff_scale_update
+ *        (xq_O, what_int, delta_what may be NULL when n_outlier = 0);
+ *        X [t x c_in] bf16 (ldx), lora_A [c_in x r] bf16, lora_B [r x c_out] bf16: read only when
+ *        lora_rank > 0 (may be NULL otherwise)
+ *   out: Y [t x c_out] fp32, leading dimension ldy
+ */
+int quaff_linear_fwd(const int8_t* Xq, const float* delta_x, const int8_t* xq_O, int64_t t, const void* Wq_packed,
+                     const float* delta_w, int64_t c_in, int64_t c_out, const int8_t* what_int,
+                     const float* delta_what, int32_t n_outlier, const uint16_t* X, int64_t ldx,
+                     const uint16_t* lora_A, const uint16_t* lora_B, int32_t lora_rank, float lora_scale, float* Y,
+                     int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Same product as quaff_linear_fwd, but the exact int32 accumulators of Eq. 9 are written instead of Y
+ * (acc1, acc2: [t x c_out] int32, dense; acc2 may be NULL).  For checking the integer path bit for bit. */
+int quaff_linear_fwd_acc(const int8_t* Xq, const int8_t* xq_O, int64_t t, const void* Wq_packed, int64_t c_in,
+                         int64_t c_out, const int8_t* what_int, int32_t n_outlier, int32_t* acc1, int32_t* acc2,
+                         void* stream);
+
+/*
+ * Backward input gradient.  The paper does not describe the backward pass; since Xhat = X s^-1 and
+ * What = s W, s cancels in the true gradient dX = dY W^T (Eq. 3), so no outlier data is needed.  delta_w lies
+ * on the contraction axis and is folded into dY before per-token quantization (the reason App.
+ * "Quantization Granularity" gives for rejecting per-input-channel steps):
+ *   G = dY * delta_w (per column), Gq, delta_g = per-token Eq. 1 of G
+ *   acc[i, k] = sum_j Gq[i, j] Wq[k, j]                                        (int32, exact)
+ *   dX[i, k] = delta_g[i] * acc[i, k] + lora_scale * sum_p (sum_j dY[i, j] B[p, j]) A[k, p]
+ *   in : dY [t x c_out] bf16 (lddy); Wq_packed, delta_w; lora_A [c_in x r], lora_B [r x c_out] bf16
+ *   out: dX [t x c_in] fp32, leading dimension lddx
+ */
+int quaff_linear_bwd_dx(const uint16_t* dY, int64_t t, int64_t lddy, const void* Wq_packed, const float* delta_w,
+                        int64_t c_in, int64_t c_out, const uint16_t* lora_A, const uint16_t* lora_B,
+                        int32_t lora_rank, float lora_scale, float* dX, int64_t lddx, void* workspace,
+                        size_t workspace_bytes, void* stream);
+
+/* Integer part of quaff_linear_bwd_dx with its intermediates exposed, for bit-exact checks:
+ * Gq [t x c_out] int8, delta_g [t] fp32, acc [t x c_in] int32 (all dense, all required). */
+int quaff_linear_bwd_dx_acc(const uint16_t* dY, int64_t t, int64_t lddy, const void* Wq_packed, const float* delta_w,
+                            int64_t c_in, int64_t c_out, int8_t* Gq, float* delta_g, int32_t* acc, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QUAFF_H_ */

@@ -1,0 +1,148 @@
+"""Thin ctypes binding of libquaff.so: the same entry points as include/quaff.h, taking torch device tensors.
+
+Argument marshalling only - every step of the path runs in the HIP kernels behind the C ABI.  PyTorch is used
+for device memory (`tensor.data_ptr()`) and the current HIP stream.  The library must have been built
+(`python -m paper_2505_14742_amd.build`); loading fails loudly otherwise - there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libquaff.so")
+
+OK, ERR_NULL, ERR_SHAPE, ERR_WORKSPACE, ERR_ALIGN, ERR_HIP = 0, -1, -2, -3, -4, -5
+
+_vp, _i64, _i32, _f32, _sz = C.c_void_p, C.c_int64, C.c_int32, C.c_float, C.c_size_t
+
+SIGNATURES = {
+    "quaff_status_string": (C.c_char_p, [C.c_int]),
+    "quaff_last_hip_error": (C.c_int, []),
+    "quaff_padded_outliers": (_i32, [_i32]),
+    "quaff_packed_weight_bytes": (_sz, [_i64, _i64]),
+    "quaff_prepare_workspace_bytes": (_sz, [_i64, _i64]),
+    "quaff_workspace_bytes": (_sz, [_i64, _i64, _i64, _i32, _i32]),
+    "quaff_prepare_weight": (C.c_int, [_vp, _i64, _i64, _i64, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "quaff_scale_update": (C.c_int, [_vp, _i64, _i64, _i64, _vp, _i32, _vp, _vp, _i64, _f32, _vp, _vp, _vp, _vp, _vp,
+                                     _vp, _sz, _vp]),
+    "quaff_quant_act": (C.c_int, [_vp, _i64, _i64, _i64, _vp, _vp, _i32, _vp, _vp, _vp, _vp]),
+    "quaff_linear_fwd": (C.c_int, [_vp, _vp, _vp, _i64, _vp, _vp, _i64, _i64, _vp, _vp, _i32, _vp, _i64, _vp, _vp,
+                                   _i32, _f32, _vp, _i64, _vp, _sz, _vp]),
+    "quaff_linear_fwd_acc": (C.c_int, [_vp, _vp, _i64, _vp, _i64, _i64, _vp, _i32, _vp, _vp, _vp]),
+    "quaff_linear_bwd_dx": (C.c_int, [_vp, _i64, _i64, _vp, _vp, _i64, _i64, _vp, _vp, _i32, _f32, _vp, _i64, _vp,
+                                      _sz, _vp]),
+    "quaff_linear_bwd_dx_acc": (C.c_int, [_vp, _i64, _i64, _vp, _vp, _i64, _i64, _vp, _vp, _vp, _vp]),
+}
+
+_lib = None
+
+
+class QuaffError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        msg = lib().quaff_status_string(status).decode()
+        if status == ERR_HIP:
+            msg += " (hipError %d)" % lib().quaff_last_hip_error()
+        super().__init__(msg)
+
+
+def lib():
+    """The loaded C-ABI library.  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libquaff.so is not built: run `python -m paper_2505_14742_amd.build` "
+                               "(there is no CPU or PyTorch fallback for this path)")
+        l = C.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(l, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = l
+    return _lib
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream():
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(status):
+    if status != OK:
+        raise QuaffError(status)
+
+
+def padded_outliers(n: int) -> int:
+    return int(lib().quaff_padded_outliers(n))
+
+
+def packed_weight_bytes(c_in: int, c_out: int) -> int:
+    return int(lib().quaff_packed_weight_bytes(c_in, c_out))
+
+
+def prepare_workspace_bytes(c_in: int, c_out: int) -> int:
+    return int(lib().quaff_prepare_workspace_bytes(c_in, c_out))
+
+
+def workspace_bytes(t: int, c_in: int, c_out: int, n_outlier: int, lora_rank: int) -> int:
+    return int(lib().quaff_workspace_bytes(t, c_in, c_out, n_outlier, lora_rank))
+
+
+def prepare_weight(W, O, Wq_packed, delta_w, W_O, wmax_O, Wq_plain, workspace):
+    c_in, c_out = W.shape
+    n = 0 if O is None else O.numel()
+    _check(lib().quaff_prepare_weight(_ptr(W), c_in, c_out, W.stride(0), _ptr(O), n, _ptr(Wq_packed), _ptr(delta_w),
+                                      _ptr(W_O), _ptr(wmax_O), _ptr(Wq_plain), _ptr(workspace),
+                                      workspace.numel() * workspace.element_size(), _stream()))
+
+
+def scale_update(X, O, W_O, wmax_O, c_out, gamma, s_O, colscale, what_int, delta_what, cmax_out, workspace):
+    t, c_in = X.shape
+    n = 0 if O is None else O.numel()
+    _check(lib().quaff_scale_update(_ptr(X), t, c_in, X.stride(0), _ptr(O), n, _ptr(W_O), _ptr(wmax_O), c_out,
+                                    float(gamma), _ptr(s_O), _ptr(colscale), _ptr(what_int), _ptr(delta_what),
+                                    _ptr(cmax_out), _ptr(workspace),
+                                    0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                    _stream()))
+
+
+def quant_act(X, colscale, O, Xq, delta, xq_O):
+    t, c = X.shape
+    n = 0 if O is None else O.numel()
+    _check(lib().quaff_quant_act(_ptr(X), t, c, X.stride(0), _ptr(colscale), _ptr(O), n, _ptr(Xq), _ptr(delta),
+                                 _ptr(xq_O), _stream()))
+
+
+def linear_fwd(Xq, delta_x, xq_O, Wq_packed, delta_w, c_in, c_out, what_int, delta_what, n_outlier, X, lora_A, lora_B,
+               lora_rank, lora_scale, Y, workspace):
+    t = Xq.shape[0]
+    _check(lib().quaff_linear_fwd(_ptr(Xq), _ptr(delta_x), _ptr(xq_O), t, _ptr(Wq_packed), _ptr(delta_w), c_in, c_out,
+                                  _ptr(what_int), _ptr(delta_what), n_outlier, _ptr(X),
+                                  0 if X is None else X.stride(0), _ptr(lora_A), _ptr(lora_B), lora_rank,
+                                  float(lora_scale), _ptr(Y), Y.stride(0), _ptr(workspace),
+                                  0 if workspace is None else workspace.numel() * workspace.element_size(), _stream()))
+
+
+def linear_fwd_acc(Xq, xq_O, Wq_packed, c_in, c_out, what_int, n_outlier, acc1, acc2):
+    t = Xq.shape[0]
+    _check(lib().quaff_linear_fwd_acc(_ptr(Xq), _ptr(xq_O), t, _ptr(Wq_packed), c_in, c_out, _ptr(what_int),
+                                      n_outlier, _ptr(acc1), _ptr(acc2), _stream()))
+
+
+def linear_bwd_dx(dY, Wq_packed, delta_w, c_in, c_out, lora_A, lora_B, lora_rank, lora_scale, dX, workspace):
+    t = dY.shape[0]
+    _check(lib().quaff_linear_bwd_dx(_ptr(dY), t, dY.stride(0), _ptr(Wq_packed), _ptr(delta_w), c_in, c_out,
+                                     _ptr(lora_A), _ptr(lora_B), lora_rank, float(lora_scale), _ptr(dX), dX.stride(0),
+                                     _ptr(workspace),
+                                     0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                     _stream()))
+
+
+def linear_bwd_dx_acc(dY, Wq_packed, delta_w, c_in, c_out, Gq, delta_g, acc):
+    t = dY.shape[0]
+    _check(lib().quaff_linear_bwd_dx_acc(_ptr(dY), t, dY.stride(0), _ptr(Wq_packed), _ptr(delta_w), c_in, c_out,
+                                         _ptr(Gq), _ptr(delta_g), _ptr(acc), _stream()))

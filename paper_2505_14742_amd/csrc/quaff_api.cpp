@@ -1,0 +1,251 @@
+// C ABI of libquaff: argument checking, workspace carving and kernel launches.  No computation happens here.
+#include "../../include/quaff.h"
+#include "quaff_internal.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int32_t pad_outliers(int32_t n) { return (n + quaff::kPadK - 1) / quaff::kPadK * quaff::kPadK; }
+
+int hip_status(hipError_t e) {
+    if (e == hipSuccess) return QUAFF_OK;
+    g_last_hip_error = (int)e;
+    return QUAFF_ERR_HIP;
+}
+
+bool dims_ok(int64_t t, int64_t c_in, int64_t c_out) {
+    const int64_t lim = (int64_t)1 << 30;
+    return t >= 1 && t < lim && c_in >= 16 && c_out >= 16 && c_in < (1 << 20) && c_out < (1 << 20) &&
+           c_in % 16 == 0 && c_out % 16 == 0;
+}
+bool rank_ok(int32_t r) { return r == 0 || (r > 0 && r <= 128 && r % 16 == 0); }
+
+struct PackedWeight {
+    int8_t* Wt;   // [c_out x c_in]
+    int8_t* Wn;   // [c_in x c_out]
+};
+PackedWeight unpack(const void* packed, int64_t c_in, int64_t c_out) {
+    int8_t* base = const_cast<int8_t*>(static_cast<const int8_t*>(packed));
+    return {base, base + align_up((size_t)c_in * (size_t)c_out)};
+}
+
+// workspace layouts -------------------------------------------------------------------------------
+size_t ws_scale(int64_t t, int32_t n) { return align_up(((size_t)quaff::scale_update_blocks(t) * n + n) * sizeof(float)); }
+struct FwdWs { size_t t_hi, t_lo, lt, total; };
+FwdWs ws_fwd(int64_t t, int64_t c_out, int32_t r) {
+    FwdWs w{};
+    size_t off = 0;
+    w.t_hi = off; off += align_up((size_t)t * r * 2);
+    w.t_lo = off; off += align_up((size_t)t * r * 2);
+    w.lt = off;   off += align_up((size_t)c_out * r * 2);
+    w.total = off;
+    return w;
+}
+struct BwdWs { size_t gq, dg, t_hi, t_lo, total; };
+BwdWs ws_bwd(int64_t t, int64_t c_out, int32_t r) {
+    BwdWs w{};
+    size_t off = 0;
+    w.gq = off;   off += align_up((size_t)t * c_out);
+    w.dg = off;   off += align_up((size_t)t * 4);
+    w.t_hi = off; off += align_up((size_t)t * r * 2);
+    w.t_lo = off; off += align_up((size_t)t * r * 2);
+    w.total = off;
+    return w;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* quaff_status_string(int status) {
+    switch (status) {
+        case QUAFF_OK: return "QUAFF_OK";
+        case QUAFF_ERR_NULL: return "QUAFF_ERR_NULL: a required pointer is NULL";
+        case QUAFF_ERR_SHAPE: return "QUAFF_ERR_SHAPE: a size is out of the supported range";
+        case QUAFF_ERR_WORKSPACE: return "QUAFF_ERR_WORKSPACE: workspace missing or too small";
+        case QUAFF_ERR_ALIGN: return "QUAFF_ERR_ALIGN: a pointer or leading dimension is misaligned";
+        case QUAFF_ERR_HIP: return "QUAFF_ERR_HIP: a HIP call failed";
+        default: return "unknown quaff status";
+    }
+}
+
+int quaff_last_hip_error(void) { return g_last_hip_error; }
+
+int32_t quaff_padded_outliers(int32_t n_outlier) { return n_outlier <= 0 ? 0 : pad_outliers(n_outlier); }
+
+size_t quaff_packed_weight_bytes(int64_t c_in, int64_t c_out) {
+    if (c_in <= 0 || c_out <= 0) return 0;
+    return 2 * align_up((size_t)c_in * (size_t)c_out);
+}
+
+size_t quaff_prepare_workspace_bytes(int64_t c_in, int64_t c_out) {
+    if (c_in <= 0 || c_out <= 0) return 0;
+    return align_up(((size_t)((c_in + 63) / 64) + 1) * (size_t)c_out * sizeof(float));
+}
+
+size_t quaff_workspace_bytes(int64_t t, int64_t c_in, int64_t c_out, int32_t n_outlier, int32_t lora_rank) {
+    if (t <= 0 || c_in <= 0 || c_out <= 0 || n_outlier < 0 || lora_rank < 0) return 0;
+    size_t a = ws_scale(t, n_outlier), b = ws_fwd(t, c_out, lora_rank).total, c = ws_bwd(t, c_out, lora_rank).total;
+    size_t m = a > b ? a : b;
+    return (m > c ? m : c) + 256;
+}
+
+int quaff_prepare_weight(const float* W, int64_t c_in, int64_t c_out, int64_t ldw, const int32_t* O, int32_t n_outlier,
+                         void* Wq_packed, float* delta_w, float* W_O, float* wmax_O, int8_t* Wq_plain, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+    if (!W || !Wq_packed || !delta_w) return QUAFF_ERR_NULL;
+    if (n_outlier > 0 && (!O || !W_O || !wmax_O)) return QUAFF_ERR_NULL;
+    if (!dims_ok(1, c_in, c_out) || n_outlier < 0 || n_outlier > c_in || ldw < c_out) return QUAFF_ERR_SHAPE;
+    if (!workspace || workspace_bytes < quaff_prepare_workspace_bytes(c_in, c_out)) return QUAFF_ERR_WORKSPACE;
+    if (!aligned16(W) || !aligned16(Wq_packed) || !aligned16(workspace)) return QUAFF_ERR_ALIGN;
+    PackedWeight pw = unpack(Wq_packed, c_in, c_out);
+    return hip_status(quaff::launch_prepare_weight(W, c_in, c_out, ldw, O, n_outlier, pw.Wt, pw.Wn, delta_w, W_O,
+                                                   wmax_O, Wq_plain, static_cast<float*>(workspace),
+                                                   static_cast<hipStream_t>(stream)));
+}
+
+int quaff_scale_update(const uint16_t* X, int64_t t, int64_t c_in, int64_t ldx, const int32_t* O, int32_t n_outlier,
+                       const float* W_O, const float* wmax_O, int64_t c_out, float gamma, float* s_O, float* colscale,
+                       int8_t* what_int, float* delta_what, float* cmax_out, void* workspace, size_t workspace_bytes,
+                       void* stream) {
+    if (n_outlier == 0) return dims_ok(t, c_in, c_out) ? QUAFF_OK : QUAFF_ERR_SHAPE;
+    if (!X || !O || !W_O || !wmax_O || !s_O || !colscale || !what_int || !delta_what) return QUAFF_ERR_NULL;
+    if (!dims_ok(t, c_in, c_out) || n_outlier < 0 || n_outlier > c_in || n_outlier > 8192 || ldx < c_in ||
+        !(gamma >= 0.0f && gamma <= 1.0f))
+        return QUAFF_ERR_SHAPE;
+    if (!workspace || workspace_bytes < ws_scale(t, n_outlier)) return QUAFF_ERR_WORKSPACE;
+    if (!aligned16(X) || !aligned16(what_int) || !aligned16(workspace) || ldx % 8 != 0) return QUAFF_ERR_ALIGN;
+    return hip_status(quaff::launch_scale_update(X, t, c_in, ldx, O, n_outlier, W_O, wmax_O, c_out, gamma, s_O,
+                                                 colscale, what_int, delta_what, cmax_out,
+                                                 static_cast<float*>(workspace), static_cast<hipStream_t>(stream)));
+}
+
+int quaff_quant_act(const uint16_t* X, int64_t t, int64_t c, int64_t ldx, const float* colscale, const int32_t* O,
+                    int32_t n_outlier, int8_t* Xq, float* delta, int8_t* xq_O, void* stream) {
+    if (!X || !Xq || !delta) return QUAFF_ERR_NULL;
+    if (xq_O && n_outlier > 0 && !O) return QUAFF_ERR_NULL;
+    if (!dims_ok(t, c, 16) || n_outlier < 0 || n_outlier > c || ldx < c) return QUAFF_ERR_SHAPE;
+    if (!aligned16(X) || !aligned16(Xq) || (colscale && !aligned16(colscale)) || ldx % 8 != 0) return QUAFF_ERR_ALIGN;
+    if (n_outlier == 0) xq_O = nullptr;
+    return hip_status(quaff::launch_quant_act(X, t, c, ldx, colscale, O, n_outlier, Xq, delta, xq_O,
+                                              static_cast<hipStream_t>(stream)));
+}
+
+static int fwd_common(const int8_t* Xq, const float* delta_x, const int8_t* xq_O, int64_t t, const void* Wq_packed,
+                      const float* delta_w, int64_t c_in, int64_t c_out, const int8_t* what_int,
+                      const float* delta_what, int32_t n_outlier, quaff::GemmArgs& g) {
+    if (!Xq || !Wq_packed) return QUAFF_ERR_NULL;
+    if (n_outlier > 0 && (!xq_O || !what_int)) return QUAFF_ERR_NULL;
+    if (!dims_ok(t, c_in, c_out) || n_outlier < 0 || n_outlier > c_in) return QUAFF_ERR_SHAPE;
+    if (!aligned16(Xq) || !aligned16(Wq_packed) || (n_outlier > 0 && (!aligned16(xq_O) || !aligned16(what_int))))
+        return QUAFF_ERR_ALIGN;
+    PackedWeight pw = unpack(Wq_packed, c_in, c_out);
+    g = quaff::GemmArgs{};
+    g.A = Xq; g.lda = c_in; g.B = pw.Wt; g.ldb = c_in;
+    g.M = t; g.N = c_out; g.K = c_in;
+    g.K2 = n_outlier > 0 ? pad_outliers(n_outlier) : 0;
+    g.A2 = xq_O; g.B2 = what_int;
+    g.row_scale = delta_x; g.col_scale = delta_w; g.col_scale2 = delta_what;
+    return QUAFF_OK;
+}
+
+int quaff_linear_fwd(const int8_t* Xq, const float* delta_x, const int8_t* xq_O, int64_t t, const void* Wq_packed,
+                     const float* delta_w, int64_t c_in, int64_t c_out, const int8_t* what_int,
+                     const float* delta_what, int32_t n_outlier, const uint16_t* X, int64_t ldx,
+                     const uint16_t* lora_A, const uint16_t* lora_B, int32_t lora_rank, float lora_scale, float* Y,
+                     int64_t ldy, void* workspace, size_t workspace_bytes, void* stream) {
+    quaff::GemmArgs g;
+    int st = fwd_common(Xq, delta_x, xq_O, t, Wq_packed, delta_w, c_in, c_out, what_int, delta_what, n_outlier, g);
+    if (st != QUAFF_OK) return st;
+    if (!delta_x || !delta_w || !Y || (n_outlier > 0 && !delta_what)) return QUAFF_ERR_NULL;
+    if (!rank_ok(lora_rank) || ldy < c_out) return QUAFF_ERR_SHAPE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (lora_rank > 0) {
+        if (!X || !lora_A || !lora_B) return QUAFF_ERR_NULL;
+        if (ldx < c_in) return QUAFF_ERR_SHAPE;
+        FwdWs w = ws_fwd(t, c_out, lora_rank);
+        if (!workspace || workspace_bytes < w.total) return QUAFF_ERR_WORKSPACE;
+        if (!aligned16(X) || !aligned16(lora_A) || !aligned16(lora_B) || !aligned16(workspace) || ldx % 8 != 0)
+            return QUAFF_ERR_ALIGN;
+        char* base = static_cast<char*>(workspace);
+        uint16_t* t_hi = reinterpret_cast<uint16_t*>(base + w.t_hi);
+        uint16_t* t_lo = reinterpret_cast<uint16_t*>(base + w.t_lo);
+        uint16_t* lt = reinterpret_cast<uint16_t*>(base + w.lt);
+        // T = scale * X A (A is [c_in x r]); B [r x c_out] -> B^T [c_out x r] for the epilogue
+        st = hip_status(quaff::launch_lora_down(X, t, c_in, ldx, lora_A, false, lora_rank, lora_scale, t_hi, t_lo,
+                                                lora_B, lt, lora_rank, c_out, s));
+        if (st != QUAFF_OK) return st;
+        g.T_hi = t_hi; g.T_lo = t_lo; g.L = lt; g.r = lora_rank;
+    }
+    g.C = Y; g.ldc = ldy;
+    return hip_status(quaff::launch_gemm(g, false, s));
+}
+
+int quaff_linear_fwd_acc(const int8_t* Xq, const int8_t* xq_O, int64_t t, const void* Wq_packed, int64_t c_in,
+                         int64_t c_out, const int8_t* what_int, int32_t n_outlier, int32_t* acc1, int32_t* acc2,
+                         void* stream) {
+    quaff::GemmArgs g;
+    int st = fwd_common(Xq, nullptr, xq_O, t, Wq_packed, nullptr, c_in, c_out, what_int, nullptr, n_outlier, g);
+    if (st != QUAFF_OK) return st;
+    if (!acc1) return QUAFF_ERR_NULL;
+    g.acc1 = acc1; g.acc2 = acc2;
+    return hip_status(quaff::launch_gemm(g, true, static_cast<hipStream_t>(stream)));
+}
+
+int quaff_linear_bwd_dx(const uint16_t* dY, int64_t t, int64_t lddy, const void* Wq_packed, const float* delta_w,
+                        int64_t c_in, int64_t c_out, const uint16_t* lora_A, const uint16_t* lora_B, int32_t lora_rank,
+                        float lora_scale, float* dX, int64_t lddx, void* workspace, size_t workspace_bytes,
+                        void* stream) {
+    if (!dY || !Wq_packed || !delta_w || !dX) return QUAFF_ERR_NULL;
+    if (lora_rank > 0 && (!lora_A || !lora_B)) return QUAFF_ERR_NULL;
+    if (!dims_ok(t, c_in, c_out) || !rank_ok(lora_rank) || lddy < c_out || lddx < c_in) return QUAFF_ERR_SHAPE;
+    BwdWs w = ws_bwd(t, c_out, lora_rank);
+    if (!workspace || workspace_bytes < w.total) return QUAFF_ERR_WORKSPACE;
+    if (!aligned16(dY) || !aligned16(Wq_packed) || !aligned16(delta_w) || !aligned16(workspace) || lddy % 8 != 0 ||
+        (lora_rank > 0 && (!aligned16(lora_A) || !aligned16(lora_B))))
+        return QUAFF_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* base = static_cast<char*>(workspace);
+    int8_t* gq = reinterpret_cast<int8_t*>(base + w.gq);
+    float* dg = reinterpret_cast<float*>(base + w.dg);
+    PackedWeight pw = unpack(Wq_packed, c_in, c_out);
+    int st = hip_status(quaff::launch_quant_act(dY, t, c_out, lddy, delta_w, nullptr, 0, gq, dg, nullptr, s));
+    if (st != QUAFF_OK) return st;
+    quaff::GemmArgs g{};
+    g.A = gq; g.lda = c_out; g.B = pw.Wn; g.ldb = c_out;
+    g.M = t; g.N = c_in; g.K = c_out;
+    g.row_scale = dg;
+    if (lora_rank > 0) {
+        uint16_t* t_hi = reinterpret_cast<uint16_t*>(base + w.t_hi);
+        uint16_t* t_lo = reinterpret_cast<uint16_t*>(base + w.t_lo);
+        // T = scale * dY B^T (B is [r x c_out], contraction-contiguous); the epilogue multiplies by A [c_in x r]
+        st = hip_status(quaff::launch_lora_down(dY, t, c_out, lddy, lora_B, true, lora_rank, lora_scale, t_hi, t_lo,
+                                                nullptr, nullptr, 0, 0, s));
+        if (st != QUAFF_OK) return st;
+        g.T_hi = t_hi; g.T_lo = t_lo; g.L = lora_A; g.r = lora_rank;
+    }
+    g.C = dX; g.ldc = lddx;
+    return hip_status(quaff::launch_gemm(g, false, s));
+}
+
+int quaff_linear_bwd_dx_acc(const uint16_t* dY, int64_t t, int64_t lddy, const void* Wq_packed, const float* delta_w,
+                            int64_t c_in, int64_t c_out, int8_t* Gq, float* delta_g, int32_t* acc, void* stream) {
+    if (!dY || !Wq_packed || !delta_w || !Gq || !delta_g || !acc) return QUAFF_ERR_NULL;
+    if (!dims_ok(t, c_in, c_out) || lddy < c_out) return QUAFF_ERR_SHAPE;
+    if (!aligned16(dY) || !aligned16(Wq_packed) || !aligned16(delta_w) || !aligned16(Gq) || lddy % 8 != 0)
+        return QUAFF_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    PackedWeight pw = unpack(Wq_packed, c_in, c_out);
+    int st = hip_status(quaff::launch_quant_act(dY, t, c_out, lddy, delta_w, nullptr, 0, Gq, delta_g, nullptr, s));
+    if (st != QUAFF_OK) return st;
+    quaff::GemmArgs g{};
+    g.A = Gq; g.lda = c_out; g.B = pw.Wn; g.ldb = c_out;
+    g.M = t; g.N = c_in; g.K = c_out;
+    g.acc1 = acc;
+    return hip_status(quaff::launch_gemm(g, true, s));
+}
+
+}  // extern "C"

@@ -1,0 +1,76 @@
+// Internal declarations shared by the translation units of libquaff (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace quaff {
+
+constexpr int kWave = 64;
+constexpr int kPadK = 64;   // outlier count is padded to the INT8 MFMA contraction step
+
+// ---- device helpers -------------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+// Eq. 1 for one value: code = clamp(rne(x * c), -127, 127) with c = 127 / max, in fp32, one rounding per op.
+__device__ __forceinline__ int rtn_code(float x, float c) {
+    float q = __builtin_rintf(__fmul_rn(x, c));
+    q = fminf(fmaxf(q, -127.0f), 127.0f);
+    return (int)q;
+}
+
+// Step size Delta = m / 127 and reciprocal step c = 127 / m of a group with absolute maximum m (both 0 if m = 0).
+__device__ __forceinline__ void rtn_steps(float m, float& delta, float& c) {
+    if (m > 0.0f) {
+        delta = __fdiv_rn(m, 127.0f);
+        c = __fdiv_rn(127.0f, m);
+    } else {
+        delta = 0.0f;
+        c = 0.0f;
+    }
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+
+// ---- host-side launchers (each enqueues on `stream`, returns a hipError_t) -------------------------
+hipError_t launch_prepare_weight(const float* W, int64_t c_in, int64_t c_out, int64_t ldw, const int32_t* O, int32_t n,
+                                 int8_t* Wt, int8_t* Wn, float* delta_w, float* W_O, float* wmax_O, int8_t* Wq_plain,
+                                 float* ws, hipStream_t stream);
+
+hipError_t launch_scale_update(const uint16_t* X, int64_t t, int64_t c_in, int64_t ldx, const int32_t* O, int32_t n,
+                               const float* W_O, const float* wmax_O, int64_t c_out, float gamma, float* s_O,
+                               float* colscale, int8_t* what_int, float* delta_what, float* cmax_out, float* ws,
+                               hipStream_t stream);
+int scale_update_blocks(int64_t t);   // number of partial-max slabs (workspace sizing)
+
+hipError_t launch_quant_act(const uint16_t* X, int64_t t, int64_t c, int64_t ldx, const float* colscale,
+                            const int32_t* O, int32_t n, int8_t* Xq, float* delta, int8_t* xq_O, hipStream_t stream);
+
+// LoRA down-projection T = scale * (X [t x c] bf16) * (L [c x r] or [r x c] bf16), kept as a bf16 hi/lo pair, and an
+// optional transposed copy of a second factor (src [rows x cols] -> dst [cols x rows]).
+hipError_t launch_lora_down(const uint16_t* X, int64_t t, int64_t c, int64_t ldx, const uint16_t* L, bool L_is_r_by_c,
+                            int32_t r, float scale, uint16_t* T_hi, uint16_t* T_lo, const uint16_t* tr_src,
+                            uint16_t* tr_dst, int64_t tr_rows, int64_t tr_cols, hipStream_t stream);
+
+struct GemmArgs {
+    // C[M x N] from A [M x K] int8 (lda) and B [N x K] int8 (ldb), both contraction-contiguous
+    const int8_t* A; int64_t lda;
+    const int8_t* B; int64_t ldb;
+    int64_t M, N, K;
+    // optional second product with its own column scale: A2 [M x K2], B2 [N x K2], K2 a multiple of 64 (0 = none)
+    const int8_t* A2; const int8_t* B2; int32_t K2;
+    const float* row_scale;    // [M]
+    const float* col_scale;    // [N] or nullptr (= 1)
+    const float* col_scale2;   // [N]
+    // optional low-rank fp term: (T_hi + T_lo) [M x r] bf16 times L [N x r] bf16 (r-contiguous)
+    const uint16_t* T_hi; const uint16_t* T_lo; const uint16_t* L; int32_t r;
+    float* C; int64_t ldc;         // fp32 output (mode 0)
+    int32_t* acc1; int32_t* acc2;  // int32 dumps (mode 1), dense ld = N
+};
+hipError_t launch_gemm(const GemmArgs& g, bool dump_acc, hipStream_t stream);
+
+}  // namespace quaff

@@ -1,0 +1,106 @@
+// Targeted momentum scaling (Eq. 7, Eq. 8 of the paper) and the dynamic outlier weights
+// what = (s_O - 1) W_O with their per-output-channel quantization (Eq. 5, Eq. 9).
+//
+// Two launches:
+//   colmax_outlier_kernel   partial column maxima of |X[:, O]| per slab of rows (a strided 2-byte gather: the
+//                           traffic is one DRAM sector per (row, outlier) whatever the kernel does), and a copy
+//                           of the previous scales so that the in-place update below has no read/write race;
+//   momentum_what_kernel    every block reduces the partial maxima and evaluates Eq. 8 / Eq. 7 for all outlier
+//                           channels (a few hundred flops, cheaper than another launch); block 0 publishes s,
+//                           1/s and cmax; then each thread requantizes one output channel of what.
+#include "quaff_internal.h"
+
+namespace quaff {
+
+constexpr int kRowsPerSlab = 8;
+constexpr int kMaxSlabs = 1024;
+
+int scale_update_blocks(int64_t t) {
+    int64_t b = (t + kRowsPerSlab - 1) / kRowsPerSlab;
+    return (int)(b < kMaxSlabs ? b : kMaxSlabs);
+}
+
+// part[slab][k] = max over the slab's rows of |X[row, O_k]|
+__global__ void __launch_bounds__(256)
+colmax_outlier_kernel(const uint16_t* __restrict__ X, int64_t t, int64_t ldx, const int32_t* __restrict__ O, int n,
+                      float* __restrict__ part, const float* __restrict__ s_O, float* __restrict__ s_prev) {
+    // rows of this slab: blockIdx.x, blockIdx.x + gridDim.x, ... in groups of kRowsPerSlab
+    const int nslab = gridDim.x;
+    if (blockIdx.x == 0)
+        for (int k = threadIdx.x; k < n; k += 256) s_prev[k] = s_O[k];
+    for (int k0 = 0; k0 < n; k0 += 256) {
+        int k = k0 + threadIdx.x;
+        float m = 0.0f;
+        if (k < n) {
+            int64_t col = O[k];
+            for (int64_t r0 = (int64_t)blockIdx.x * kRowsPerSlab; r0 < t; r0 += (int64_t)nslab * kRowsPerSlab) {
+                int64_t r1 = r0 + kRowsPerSlab < t ? r0 + kRowsPerSlab : t;
+                for (int64_t r = r0; r < r1; ++r)
+                    m = fmaxf(m, fabsf(bf16_bits_to_f32(X[r * ldx + col])));
+            }
+            part[(int64_t)blockIdx.x * n + k] = m;
+        }
+    }
+}
+
+__global__ void __launch_bounds__(256)
+momentum_what_kernel(const float* __restrict__ part, int nslab, int n, int n_pad, const float* __restrict__ wmax_O,
+                     const float* __restrict__ s_prev, float gamma, const int32_t* __restrict__ O,
+                     float* __restrict__ s_O, float* __restrict__ colscale, float* __restrict__ cmax_out,
+                     const float* __restrict__ W_O, int64_t c_out, int8_t* __restrict__ what_int,
+                     float* __restrict__ delta_what) {
+    extern __shared__ float sm1[];   // [n] : s_k - 1
+    for (int k = threadIdx.x; k < n; k += 256) {
+        float cmax = 0.0f;
+        for (int b = 0; b < nslab; ++b) cmax = fmaxf(cmax, part[(int64_t)b * n + k]);
+        float beta = 1.0f;
+        float wmax = wmax_O[k];
+        if (wmax > 0.0f) beta = fmaxf(1.0f, __builtin_sqrtf(__fdiv_rn(cmax, wmax)));          // Eq. 8
+        float s = __fadd_rn(__fmul_rn(gamma, s_prev[k]), __fmul_rn(__fsub_rn(1.0f, gamma), beta));   // Eq. 7
+        sm1[k] = __fsub_rn(s, 1.0f);
+        if (blockIdx.x == 0) {
+            s_O[k] = s;
+            colscale[O[k]] = __fdiv_rn(1.0f, s);
+            if (cmax_out) cmax_out[k] = cmax;
+        }
+    }
+    __syncthreads();
+    int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= c_out) return;
+    float m = 0.0f;
+    for (int k = 0; k < n; ++k) m = fmaxf(m, fabsf(__fmul_rn(sm1[k], W_O[(int64_t)k * c_out + j])));
+    float d, c;
+    rtn_steps(m, d, c);
+    delta_what[j] = d;
+    // row j of what_int holds n_pad codes; packed four at a time
+    uint32_t* dst = reinterpret_cast<uint32_t*>(what_int + j * n_pad);
+    for (int k4 = 0; k4 < n_pad; k4 += 4) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            int k = k4 + u;
+            int q = 0;
+            if (k < n) q = rtn_code(__fmul_rn(sm1[k], W_O[(int64_t)k * c_out + j]), c);
+            w |= (uint32_t)(q & 0xFF) << (8 * u);
+        }
+        dst[k4 >> 2] = w;
+    }
+}
+
+hipError_t launch_scale_update(const uint16_t* X, int64_t t, int64_t c_in, int64_t ldx, const int32_t* O, int32_t n,
+                               const float* W_O, const float* wmax_O, int64_t c_out, float gamma, float* s_O,
+                               float* colscale, int8_t* what_int, float* delta_what, float* cmax_out, float* ws,
+                               hipStream_t stream) {
+    (void)c_in;
+    int nslab = scale_update_blocks(t);
+    int n_pad = (n + kPadK - 1) / kPadK * kPadK;
+    float* part = ws;                          // [nslab x n]
+    float* s_prev = ws + (int64_t)nslab * n;   // [n]
+    hipLaunchKernelGGL(colmax_outlier_kernel, dim3(nslab), dim3(256), 0, stream, X, t, ldx, O, n, part, s_O, s_prev);
+    hipLaunchKernelGGL(momentum_what_kernel, dim3((unsigned)((c_out + 255) / 256)), dim3(256), n * sizeof(float),
+                       stream, part, nslab, n, n_pad, wmax_O, s_prev, gamma, O, s_O, colscale, cmax_out, W_O, c_out,
+                       what_int, delta_what);
+    return hipGetLastError();
+}
+
+}  // namespace quaff

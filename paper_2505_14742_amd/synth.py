@@ -15,7 +15,9 @@ between steps (Fig. 2 caption, App. "static vs dynamic scale").
 """
 from __future__ import annotations
 
+import os
 from dataclasses import dataclass, field
+
 import numpy as np
 
 BASE_SEED = 250514742
@@ -154,11 +156,27 @@ def projection(config: int, name: str) -> Projection:
 _S_OUTLIER_IDX, _S_MULT0, _S_DRIFT, _S_W, _S_A, _S_B, _S_X, _S_DY = 1, 2, 3, 4, 5, 6, 100, 5000
 
 
-def _chunked(fn, seed, stream, count, chunk=1 << 22):
+_POOL = None
+
+
+def _pool():
+    global _POOL
+    if _POOL is None:
+        from concurrent.futures import ThreadPoolExecutor
+        _POOL = ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1))
+    return _POOL
+
+
+def _chunked(fn, seed, stream, count, start=0, chunk=1 << 20):
+    """fp32 array of `count` draws of fn for counters start..start+count-1 (chunks are drawn in parallel;
+    a value depends only on its counter, so the result does not depend on the chunking)."""
     out = np.empty(count, dtype=np.float32)
-    for s in range(0, count, chunk):
+
+    def work(s):
         e = min(count, s + chunk)
-        out[s:e] = fn(seed, stream, e - s, s)
+        out[s:e] = fn(seed, stream, e - s, start + s)
+
+    list(_pool().map(work, range(0, count, chunk)))
     return out
 
 
@@ -228,12 +246,7 @@ def activations(p: Projection, step: int, rows: slice | None = None) -> np.ndarr
     fn = student_t3 if p.dist == "student_t3" else normal
     r0, r1 = (0, p.t) if rows is None else (rows.start, rows.stop)
     base = p.c_in * p.t * step + r0 * p.c_in
-    x = np.empty((r1 - r0) * p.c_in, dtype=np.float32)
-    chunk = 1 << 22
-    for s in range(0, x.size, chunk):
-        e = min(x.size, s + chunk)
-        x[s:e] = fn(p.seed, _S_X, e - s, base + s)
-    x = x.reshape(r1 - r0, p.c_in)
+    x = _chunked(fn, p.seed, _S_X, (r1 - r0) * p.c_in, base).reshape(r1 - r0, p.c_in)
     o = outlier_indices(p)
     if o.size:
         x[:, o] *= outlier_multipliers(p, step).astype(np.float32)[None, :]
