@@ -76,7 +76,7 @@ size_t quaff_workspace_bytes(int64_t t, int64_t c_in, int64_t c_out, int32_t n_o
  *        W_O        [n_outlier x c_out] fp32 copy of the O rows of W       (may be NULL when n_outlier = 0)
  *        wmax_O     [n_outlier] fp32, max_j |W_O[k, j]| (the max|W_i| of Eq. 8) (may be NULL when n_outlier = 0)
  *        Wq_plain   optional [c_in x c_out] int8 codes in the paper's layout (NULL to skip)
- * `workspace` must hold at least 4 * c_out * ceil(c_in / 64) bytes... see quaff_prepare_workspace_bytes.
+ * `workspace` holds partial column maxima; it must be at least quaff_prepare_workspace_bytes(c_in, c_out) bytes.
  */
 size_t quaff_prepare_workspace_bytes(int64_t c_in, int64_t c_out);
 int quaff_prepare_weight(const float* W, int64_t c_in, int64_t c_out, int64_t ldw, const int32_t* O,
@@ -162,6 +162,20 @@ int quaff_linear_bwd_dx(const uint16_t* dY, int64_t t, int64_t lddy, const void*
  * Gq [t x c_out] int8, delta_g [t] fp32, acc [t x c_in] int32 (all dense, all required). */
 int quaff_linear_bwd_dx_acc(const uint16_t* dY, int64_t t, int64_t lddy, const void* Wq_packed, const float* delta_w,
                             int64_t c_in, int64_t c_out, int8_t* Gq, float* delta_g, int32_t* acc, void* stream);
+
+/*
+ * Optional per-launch kernel timing for benchmarks (not part of the method).  While enabled, every kernel the
+ * library launches is bracketed by a pair of HIP events on the caller's stream; this perturbs end-to-end time, so
+ * whole-step timing is taken with profiling off.  State is process-wide and guarded by a mutex.
+ *   quaff_profile_enable(on)    drop all records, then start (on != 0) or stop recording; returns QUAFF_OK
+ *   quaff_profile_collect()     wait for the recorded events; returns the number of recorded launches, -1 on error
+ *   quaff_profile_launch(i,..)  kind and duration (ms) of the i-th recorded launch, in launch order
+ *   quaff_profile_kind_name(k)  static name of a kernel kind
+ */
+int quaff_profile_enable(int on);
+int64_t quaff_profile_collect(void);
+int quaff_profile_launch(int64_t index, int* kind, float* ms);
+const char* quaff_profile_kind_name(int kind);
 
 #ifdef __cplusplus
 }

@@ -33,6 +33,10 @@ SIGNATURES = {
     "quaff_linear_bwd_dx": (C.c_int, [_vp, _i64, _i64, _vp, _vp, _i64, _i64, _vp, _vp, _i32, _f32, _vp, _i64, _vp,
                                       _sz, _vp]),
     "quaff_linear_bwd_dx_acc": (C.c_int, [_vp, _i64, _i64, _vp, _vp, _i64, _i64, _vp, _vp, _vp, _vp]),
+    "quaff_profile_enable": (C.c_int, [C.c_int]),
+    "quaff_profile_collect": (_i64, []),
+    "quaff_profile_launch": (C.c_int, [_i64, C.POINTER(C.c_int), C.POINTER(C.c_float)]),
+    "quaff_profile_kind_name": (C.c_char_p, [C.c_int]),
 }
 
 _lib = None
@@ -146,3 +150,20 @@ def linear_bwd_dx_acc(dY, Wq_packed, delta_w, c_in, c_out, Gq, delta_g, acc):
     t = dY.shape[0]
     _check(lib().quaff_linear_bwd_dx_acc(_ptr(dY), t, dY.stride(0), _ptr(Wq_packed), _ptr(delta_w), c_in, c_out,
                                          _ptr(Gq), _ptr(delta_g), _ptr(acc), _stream()))
+
+
+def profile_enable(on: bool):
+    _check(lib().quaff_profile_enable(1 if on else 0))
+
+
+def profile_launches():
+    """[(kernel kind name, milliseconds), ...] of every launch recorded since profile_enable(True), in order."""
+    n = int(lib().quaff_profile_collect())
+    if n < 0:
+        raise QuaffError(ERR_HIP)
+    out = []
+    kind, ms = C.c_int(), C.c_float()
+    for i in range(n):
+        _check(lib().quaff_profile_launch(i, C.byref(kind), C.byref(ms)))
+        out.append((lib().quaff_profile_kind_name(kind.value).decode(), float(ms.value)))
+    return out

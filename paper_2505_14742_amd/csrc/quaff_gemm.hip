@@ -191,6 +191,7 @@ static hipError_t launch_cfg(const GemmArgs& g, bool dump, hipStream_t stream) {
 }
 
 hipError_t launch_gemm(const GemmArgs& g, bool dump_acc, hipStream_t stream) {
+    ProfScope prof(K_GEMM, stream);
     // large tiles when they still give every compute unit work, smaller ones otherwise
     int64_t big_tiles = ((g.M + 255) / 256) * ((g.N + 255) / 256);
     if (big_tiles >= 200) return launch_cfg<256, 256, 64, 2, 2>(g, dump_acc, stream);

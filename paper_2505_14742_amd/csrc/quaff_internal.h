@@ -36,6 +36,17 @@ __device__ __forceinline__ float wave_max(float v) {
     return v;
 }
 
+// ---- optional per-launch timing (see quaff_profile_* in the C ABI) ------------------------------------
+enum KernelKind { K_PREPARE = 0, K_COLMAX, K_MOMENTUM, K_QUANT, K_LORA, K_GEMM, KERNEL_KINDS };
+class ProfScope {
+public:
+    ProfScope(int kind, hipStream_t stream);
+    ~ProfScope();
+private:
+    hipStream_t stream_;
+    int idx_;
+};
+
 // ---- host-side launchers (each enqueues on `stream`, returns a hipError_t) -------------------------
 hipError_t launch_prepare_weight(const float* W, int64_t c_in, int64_t c_out, int64_t ldw, const int32_t* O, int32_t n,
                                  int8_t* Wt, int8_t* Wn, float* delta_w, float* W_O, float* wmax_O, int8_t* Wq_plain,

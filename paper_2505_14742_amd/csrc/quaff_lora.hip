@@ -114,6 +114,7 @@ static void dispatch(int R16, dim3 grid, hipStream_t stream, const uint16_t* X, 
 hipError_t launch_lora_down(const uint16_t* X, int64_t t, int64_t c, int64_t ldx, const uint16_t* L, bool L_is_r_by_c,
                             int32_t r, float scale, uint16_t* T_hi, uint16_t* T_lo, const uint16_t* tr_src,
                             uint16_t* tr_dst, int64_t tr_rows, int64_t tr_cols, hipStream_t stream) {
+    ProfScope prof(K_LORA, stream);
     int row_blocks = (int)((t + 15) / 16);
     int tr_blocks = 0;
     if (tr_src) {

@@ -67,6 +67,7 @@ outlier_rows_kernel(const float* __restrict__ W, int64_t c_out, int64_t ldw, con
 hipError_t launch_prepare_weight(const float* W, int64_t c_in, int64_t c_out, int64_t ldw, const int32_t* O, int32_t n,
                                  int8_t* Wt, int8_t* Wn, float* delta_w, float* W_O, float* wmax_O, int8_t* Wq_plain,
                                  float* ws, hipStream_t stream) {
+    ProfScope prof(K_PREPARE, stream);
     int nslab = (int)((c_in + kSlab - 1) / kSlab);
     float* part = ws;                               // [nslab x c_out]
     float* recip = ws + (int64_t)nslab * c_out;     // [c_out]

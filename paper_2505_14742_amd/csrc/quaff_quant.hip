@@ -153,6 +153,7 @@ static void launch_rows(const uint16_t* X, int64_t t, int c, int64_t ldx, const 
 
 hipError_t launch_quant_act(const uint16_t* X, int64_t t, int64_t c64, int64_t ldx, const float* cs, const int32_t* O,
                             int32_t n, int8_t* Xq, float* delta, int8_t* xq_O, hipStream_t stream) {
+    ProfScope prof(K_QUANT, stream);
     const int c = (int)c64;
     const int n_pad = (n + kPadK - 1) / kPadK * kPadK;
     const int vec = (c + 7) / 8;   // 16-byte vectors per row

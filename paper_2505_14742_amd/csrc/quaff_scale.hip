@@ -96,7 +96,11 @@ hipError_t launch_scale_update(const uint16_t* X, int64_t t, int64_t c_in, int64
     int n_pad = (n + kPadK - 1) / kPadK * kPadK;
     float* part = ws;                          // [nslab x n]
     float* s_prev = ws + (int64_t)nslab * n;   // [n]
-    hipLaunchKernelGGL(colmax_outlier_kernel, dim3(nslab), dim3(256), 0, stream, X, t, ldx, O, n, part, s_O, s_prev);
+    {
+        ProfScope prof(K_COLMAX, stream);
+        hipLaunchKernelGGL(colmax_outlier_kernel, dim3(nslab), dim3(256), 0, stream, X, t, ldx, O, n, part, s_O, s_prev);
+    }
+    ProfScope prof(K_MOMENTUM, stream);
     hipLaunchKernelGGL(momentum_what_kernel, dim3((unsigned)((c_out + 255) / 256)), dim3(256), n * sizeof(float),
                        stream, part, nslab, n, n_pad, wmax_O, s_prev, gamma, O, s_O, colscale, cmax_out, W_O, c_out,
                        what_int, delta_what);
