@@ -3,11 +3,12 @@
 // Forward: X is the layer input and L = A [c_in x r].  Backward: X is dY and L = B^T, given as B [r x c_out].
 //
 // HBM-bound skinny product (reads X once).  bf16 MFMA 16x16x32 with fp32 accumulation; a workgroup owns 16 rows,
-// its four wavefronts take interleaved contraction steps and are summed in a fixed order, so the result is
-// deterministic.  T is handed to the GEMM epilogue as a bf16 pair (hi + lo, 16 significant bits) so that the
-// up-projection can also run on the bf16 MFMA without losing the fp32 accumulation's accuracy.
-// Extra workgroups of the same launch write the transposed copy of the other factor that the epilogue reads
-// contraction-contiguous.
+// its eight wavefronts take interleaved 32-wide contraction steps and are summed in a fixed order, so the result
+// is deterministic.  When L is stored [c x r] the MFMA needs it transposed: each wavefront stages its own
+// 32 x r slice through a private piece of LDS (coalesced 16-byte loads in, 2-byte scatter, 16-byte fragment out).
+// T is handed to the GEMM epilogue as a bf16 pair (hi + lo, 16 significant bits) so that the up-projection can
+// also run on the bf16 MFMA without losing the fp32 accumulation's accuracy.  Extra workgroups of the same launch
+// write the transposed copy of the other factor that the epilogue reads contraction-contiguous.
 #include "quaff_internal.h"
 
 namespace quaff {
@@ -16,6 +17,8 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+constexpr int kLoraWaves = 8;
+
 __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
     uint32_t u = __float_as_uint(f);
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
@@ -23,22 +26,25 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
 
 // R16 = r / 16 column blocks of T.  L_RC: L is [r x c] (contraction-contiguous) else [c x r].
 template <int R16, bool L_RC>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(64 * kLoraWaves)
 lora_down_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx, const uint16_t* __restrict__ L,
                  float scale, uint16_t* __restrict__ T_hi, uint16_t* __restrict__ T_lo, int row_blocks,
                  const uint16_t* __restrict__ tr_src, uint16_t* __restrict__ tr_dst, int64_t tr_rows, int64_t tr_cols) {
     constexpr int r = R16 * 16;
+    constexpr int NT = 64 * kLoraWaves;
+    constexpr int TROW = 40;                       // padded row (in bf16) of the transposed slice: 32 + 8
     if ((int)blockIdx.x >= row_blocks) {
         // transposed copy: dst [cols x rows] <- src [rows x cols]
         int64_t total = tr_rows * tr_cols;
         int64_t nb = gridDim.x - row_blocks;
-        for (int64_t e = ((int64_t)blockIdx.x - row_blocks) * 256 + threadIdx.x; e < total; e += nb * 256) {
+        for (int64_t e = ((int64_t)blockIdx.x - row_blocks) * NT + threadIdx.x; e < total; e += nb * NT) {
             int64_t col = e / tr_rows, row = e % tr_rows;
             tr_dst[e] = tr_src[row * tr_cols + col];
         }
         return;
     }
-    __shared__ float red[4][R16][64][4];
+    __shared__ float red[kLoraWaves][R16][64][4];
+    __shared__ __attribute__((aligned(16))) uint16_t lt[L_RC ? 1 : kLoraWaves][L_RC ? 1 : r][L_RC ? 8 : TROW];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 15, g = lane >> 4;
     const int64_t row = (int64_t)blockIdx.x * 16 + m;
@@ -49,24 +55,35 @@ lora_down_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx, 
 #pragma unroll
     for (int b = 0; b < R16; ++b) acc[b] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    for (int k0 = wave * 32; k0 < c; k0 += 4 * 32) {
+    for (int k0 = wave * 32; k0 < c; k0 += kLoraWaves * 32) {
         const int k = k0 + g * 8;          // this lane's eight contraction indices
         u32x4 xa = (u32x4){0, 0, 0, 0};
         if (live && k < c) xa = *reinterpret_cast<const u32x4*>(xrow + k);
+        if (!L_RC) {
+            // stage L[k0 .. k0+32) x r transposed into this wavefront's LDS slice: lt[p][kk]
+            constexpr int VEC = 32 * r / 8;                 // 16-byte vectors in the slice
+#pragma unroll
+            for (int v0 = 0; v0 < VEC; v0 += 64) {
+                int v = v0 + lane;
+                int kk = v / (r / 8), p0 = (v % (r / 8)) * 8;
+                u32x4 lv = (u32x4){0, 0, 0, 0};
+                if (v < VEC && k0 + kk < c) lv = *reinterpret_cast<const u32x4*>(L + (int64_t)(k0 + kk) * r + p0);
+                if (v < VEC) {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        lt[wave][p0 + 2 * u][kk] = (uint16_t)(lv[u] & 0xFFFFu);
+                        lt[wave][p0 + 2 * u + 1][kk] = (uint16_t)(lv[u] >> 16);
+                    }
+                }
+            }
+        }
 #pragma unroll
         for (int b = 0; b < R16; ++b) {
             u32x4 lb = (u32x4){0, 0, 0, 0};
-            if (k < c) {
-                if (L_RC) {
-                    lb = *reinterpret_cast<const u32x4*>(L + (int64_t)(b * 16 + m) * c + k);
-                } else {
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        uint32_t lo = L[(int64_t)(k + 2 * u) * r + b * 16 + m];
-                        uint32_t hi = L[(int64_t)(k + 2 * u + 1) * r + b * 16 + m];
-                        lb[u] = lo | (hi << 16);
-                    }
-                }
+            if (L_RC) {
+                if (k < c) lb = *reinterpret_cast<const u32x4*>(L + (int64_t)(b * 16 + m) * c + k);
+            } else {
+                lb = *reinterpret_cast<const u32x4*>(&lt[wave][b * 16 + m][g * 8]);
             }
             acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xa),
                                                              __builtin_bit_cast(bf16x8, lb), acc[b], 0, 0, 0);
@@ -77,22 +94,20 @@ lora_down_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx, 
 #pragma unroll
         for (int v = 0; v < 4; ++v) red[wave][b][lane][v] = acc[b][v];
     __syncthreads();
-    if (wave == 0) {
+    // fixed-order sum over the wavefronts; element v of lane (m, g) is T[row0 + 4 g + v][16 b + m]
+    for (int e = threadIdx.x; e < R16 * 64 * 4; e += NT) {
+        int v = e & 3, ln = (e >> 2) & 63, b = e >> 8;
+        float s = 0.0f;
 #pragma unroll
-        for (int b = 0; b < R16; ++b)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                // accumulator element v of lane (m, g) is T[row0 + 4 g + v][16 b + m]
-                float s = ((red[0][b][lane][v] + red[1][b][lane][v]) + red[2][b][lane][v]) + red[3][b][lane][v];
-                s = s * scale;
-                int64_t orow = (int64_t)blockIdx.x * 16 + g * 4 + v;
-                if (orow < t) {
-                    uint32_t hi = f32_to_bf16_rne(s);
-                    float rest = s - __uint_as_float(hi << 16);
-                    T_hi[orow * r + b * 16 + m] = (uint16_t)hi;
-                    T_lo[orow * r + b * 16 + m] = (uint16_t)f32_to_bf16_rne(rest);
-                }
-            }
+        for (int w = 0; w < kLoraWaves; ++w) s += red[w][b][ln][v];
+        s = s * scale;
+        int64_t orow = (int64_t)blockIdx.x * 16 + (ln >> 4) * 4 + v;
+        if (orow < t) {
+            uint32_t hi = f32_to_bf16_rne(s);
+            float rest = s - __uint_as_float(hi << 16);
+            T_hi[orow * r + b * 16 + (ln & 15)] = (uint16_t)hi;
+            T_lo[orow * r + b * 16 + (ln & 15)] = (uint16_t)f32_to_bf16_rne(rest);
+        }
     }
 }
 
@@ -102,8 +117,8 @@ static void dispatch(int R16, dim3 grid, hipStream_t stream, const uint16_t* X, 
                      const uint16_t* tr_src, uint16_t* tr_dst, int64_t tr_rows, int64_t tr_cols) {
 #define QUAFF_LORA(N)                                                                                              \
     case N:                                                                                                        \
-        hipLaunchKernelGGL((lora_down_kernel<N, L_RC>), grid, dim3(256), 0, stream, X, t, c, ldx, L, scale, T_hi,  \
-                           T_lo, row_blocks, tr_src, tr_dst, tr_rows, tr_cols);                                    \
+        hipLaunchKernelGGL((lora_down_kernel<N, L_RC>), grid, dim3(64 * kLoraWaves), 0, stream, X, t, c, ldx, L,   \
+                           scale, T_hi, T_lo, row_blocks, tr_src, tr_dst, tr_rows, tr_cols);                       \
         break;
     switch (R16) {
         QUAFF_LORA(1) QUAFF_LORA(2) QUAFF_LORA(3) QUAFF_LORA(4) QUAFF_LORA(5) QUAFF_LORA(6) QUAFF_LORA(7) QUAFF_LORA(8)
@@ -118,8 +133,8 @@ hipError_t launch_lora_down(const uint16_t* X, int64_t t, int64_t c, int64_t ldx
     int row_blocks = (int)((t + 15) / 16);
     int tr_blocks = 0;
     if (tr_src) {
-        int64_t b = (tr_rows * tr_cols + 1023) / 1024;
-        tr_blocks = (int)(b < 256 ? (b > 0 ? b : 1) : 256);
+        int64_t b = (tr_rows * tr_cols + 2047) / 2048;
+        tr_blocks = (int)(b < 128 ? (b > 0 ? b : 1) : 128);
     }
     dim3 grid(row_blocks + tr_blocks);
     if (L_is_r_by_c)

@@ -8,54 +8,63 @@
 //   momentum_what_kernel    every block reduces the partial maxima and evaluates Eq. 8 / Eq. 7 for all outlier
 //                           channels (a few hundred flops, cheaper than another launch); block 0 publishes s,
 //                           1/s and cmax; then each thread requantizes one output channel of what.
+// Maxima of non-negative floats are taken on their bit patterns (same order as unsigned integers) with LDS
+// atomics, which is exact and independent of the order of arrival.
 #include "quaff_internal.h"
 
 namespace quaff {
 
-constexpr int kRowsPerSlab = 8;
-constexpr int kMaxSlabs = 1024;
+constexpr int kRowsPerSlab = 16;
+constexpr int kMaxSlabs = 256;
 
 int scale_update_blocks(int64_t t) {
     int64_t b = (t + kRowsPerSlab - 1) / kRowsPerSlab;
     return (int)(b < kMaxSlabs ? b : kMaxSlabs);
 }
 
-// part[slab][k] = max over the slab's rows of |X[row, O_k]|
+// part[slab][k] = max over the slab's rows of |X[row, O_k]|; slab s owns row groups s, s + nslab, ...
 __global__ void __launch_bounds__(256)
 colmax_outlier_kernel(const uint16_t* __restrict__ X, int64_t t, int64_t ldx, const int32_t* __restrict__ O, int n,
-                      float* __restrict__ part, const float* __restrict__ s_O, float* __restrict__ s_prev) {
-    // rows of this slab: blockIdx.x, blockIdx.x + gridDim.x, ... in groups of kRowsPerSlab
+                      uint32_t* __restrict__ part, const float* __restrict__ s_O, float* __restrict__ s_prev) {
+    extern __shared__ uint32_t smax[];   // [n]
     const int nslab = gridDim.x;
+    for (int k = threadIdx.x; k < n; k += 256) smax[k] = 0u;
     if (blockIdx.x == 0)
         for (int k = threadIdx.x; k < n; k += 256) s_prev[k] = s_O[k];
-    for (int k0 = 0; k0 < n; k0 += 256) {
-        int k = k0 + threadIdx.x;
-        float m = 0.0f;
-        if (k < n) {
-            int64_t col = O[k];
-            for (int64_t r0 = (int64_t)blockIdx.x * kRowsPerSlab; r0 < t; r0 += (int64_t)nslab * kRowsPerSlab) {
-                int64_t r1 = r0 + kRowsPerSlab < t ? r0 + kRowsPerSlab : t;
-                for (int64_t r = r0; r < r1; ++r)
-                    m = fmaxf(m, fabsf(bf16_bits_to_f32(X[r * ldx + col])));
+    __syncthreads();
+    const int per_group = kRowsPerSlab * n;
+    for (int64_t r0 = (int64_t)blockIdx.x * kRowsPerSlab; r0 < t; r0 += (int64_t)nslab * kRowsPerSlab) {
+        for (int e = threadIdx.x; e < per_group; e += 256) {
+            int r = e / n, k = e - r * n;
+            int64_t row = r0 + r;
+            if (row < t) {
+                uint32_t mag = ((uint32_t)X[row * ldx + O[k]] & 0x7FFFu) << 16;   // |x| as fp32 bits
+                atomicMax(&smax[k], mag);
             }
-            part[(int64_t)blockIdx.x * n + k] = m;
         }
     }
+    __syncthreads();
+    for (int k = threadIdx.x; k < n; k += 256) part[(int64_t)blockIdx.x * n + k] = smax[k];
 }
 
 __global__ void __launch_bounds__(256)
-momentum_what_kernel(const float* __restrict__ part, int nslab, int n, int n_pad, const float* __restrict__ wmax_O,
+momentum_what_kernel(const uint32_t* __restrict__ part, int nslab, int n, int n_pad, const float* __restrict__ wmax_O,
                      const float* __restrict__ s_prev, float gamma, const int32_t* __restrict__ O,
                      float* __restrict__ s_O, float* __restrict__ colscale, float* __restrict__ cmax_out,
                      const float* __restrict__ W_O, int64_t c_out, int8_t* __restrict__ what_int,
                      float* __restrict__ delta_what) {
-    extern __shared__ float sm1[];   // [n] : s_k - 1
+    extern __shared__ float sm1[];                                  // [n] : s_k - 1
+    uint32_t* smax = reinterpret_cast<uint32_t*>(sm1 + n);         // [n]
+    for (int k = threadIdx.x; k < n; k += 256) smax[k] = 0u;
+    __syncthreads();
+    const int total = nslab * n;
+    for (int e = threadIdx.x; e < total; e += 256) atomicMax(&smax[e % n], part[e]);
+    __syncthreads();
     for (int k = threadIdx.x; k < n; k += 256) {
-        float cmax = 0.0f;
-        for (int b = 0; b < nslab; ++b) cmax = fmaxf(cmax, part[(int64_t)b * n + k]);
+        float cmax = __uint_as_float(smax[k]);
         float beta = 1.0f;
         float wmax = wmax_O[k];
-        if (wmax > 0.0f) beta = fmaxf(1.0f, __builtin_sqrtf(__fdiv_rn(cmax, wmax)));          // Eq. 8
+        if (wmax > 0.0f) beta = fmaxf(1.0f, __builtin_sqrtf(__fdiv_rn(cmax, wmax)));                 // Eq. 8
         float s = __fadd_rn(__fmul_rn(gamma, s_prev[k]), __fmul_rn(__fsub_rn(1.0f, gamma), beta));   // Eq. 7
         sm1[k] = __fsub_rn(s, 1.0f);
         if (blockIdx.x == 0) {
@@ -72,18 +81,19 @@ momentum_what_kernel(const float* __restrict__ part, int nslab, int n, int n_pad
     float d, c;
     rtn_steps(m, d, c);
     delta_what[j] = d;
-    // row j of what_int holds n_pad codes; packed four at a time
-    uint32_t* dst = reinterpret_cast<uint32_t*>(what_int + j * n_pad);
-    for (int k4 = 0; k4 < n_pad; k4 += 4) {
-        uint32_t w = 0;
+    // row j of what_int holds n_pad codes; written sixteen at a time
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    u32x4* dst = reinterpret_cast<u32x4*>(what_int + j * n_pad);
+    for (int k16 = 0; k16 < n_pad; k16 += 16) {
+        u32x4 w = (u32x4){0, 0, 0, 0};
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            int k = k4 + u;
+        for (int u = 0; u < 16; ++u) {
+            int k = k16 + u;
             int q = 0;
             if (k < n) q = rtn_code(__fmul_rn(sm1[k], W_O[(int64_t)k * c_out + j]), c);
-            w |= (uint32_t)(q & 0xFF) << (8 * u);
+            w[u >> 2] |= (uint32_t)(q & 0xFF) << (8 * (u & 3));
         }
-        dst[k4 >> 2] = w;
+        dst[k16 >> 4] = w;
     }
 }
 
@@ -94,16 +104,17 @@ hipError_t launch_scale_update(const uint16_t* X, int64_t t, int64_t c_in, int64
     (void)c_in;
     int nslab = scale_update_blocks(t);
     int n_pad = (n + kPadK - 1) / kPadK * kPadK;
-    float* part = ws;                          // [nslab x n]
-    float* s_prev = ws + (int64_t)nslab * n;   // [n]
+    uint32_t* part = reinterpret_cast<uint32_t*>(ws);   // [nslab x n]
+    float* s_prev = ws + (int64_t)nslab * n;            // [n]
     {
         ProfScope prof(K_COLMAX, stream);
-        hipLaunchKernelGGL(colmax_outlier_kernel, dim3(nslab), dim3(256), 0, stream, X, t, ldx, O, n, part, s_O, s_prev);
+        hipLaunchKernelGGL(colmax_outlier_kernel, dim3(nslab), dim3(256), n * sizeof(uint32_t), stream, X, t, ldx, O,
+                           n, part, s_O, s_prev);
     }
     ProfScope prof(K_MOMENTUM, stream);
-    hipLaunchKernelGGL(momentum_what_kernel, dim3((unsigned)((c_out + 255) / 256)), dim3(256), n * sizeof(float),
-                       stream, part, nslab, n, n_pad, wmax_O, s_prev, gamma, O, s_O, colscale, cmax_out, W_O, c_out,
-                       what_int, delta_what);
+    hipLaunchKernelGGL(momentum_what_kernel, dim3((unsigned)((c_out + 255) / 256)), dim3(256),
+                       2 * n * sizeof(float), stream, part, nslab, n, n_pad, wmax_O, s_prev, gamma, O, s_O, colscale,
+                       cmax_out, W_O, c_out, what_int, delta_what);
     return hipGetLastError();
 }
 
