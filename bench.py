@@ -192,32 +192,50 @@ def main():
         "kernels": kernels,
     }
 
+    # measured ceilings next to the published peaks (register-only MFMA loop, streaming copy)
+    mf_const, clk_const = q.microbench_mfma_i8(False)
+    mf_rand, clk_rand = q.microbench_mfma_i8(True)
+    out["measured_ceilings"] = {
+        "mfma_i8_register_loop_constant_operands": {"tops": round(mf_const, 1), "clock_mhz": round(clk_const)},
+        "mfma_i8_register_loop_random_operands": {"tops": round(mf_rand, 1), "clock_mhz": round(clk_rand)},
+        "stream_copy_GBs_read_plus_write": round(q.microbench_copy(1 << 30), 1),
+        "gemm_frac_of_random_operand_mfma_rate": round(gemm_tops / mf_rand, 4)}
+
     if not args.no_cpu_baseline:
+        # the oracle as it stands on the host cores: whole steps of the same workload (all projections, all rows),
+        # repeated on successive batches until about 10 s of CPU work have been timed
         from oracle import api as orc
-        L = layers[-1]    # bounded sample: the last projection of the workload, one full step on the oracle
-        p = L["p"]
-        W, O = synth.weight(p), synth.outlier_indices(p)
-        A, B = synth.lora(p)
-        Wq, dw = orc.weight_quantize(W)
-        W_O, wmax = orc.outlier_rows(W, O)
-        X = synth.activations(p, 0)
-        dY = synth.out_grad(p, 0) if p.backward else None
-        rows = min(p.t, 1024)
-        t0 = time.perf_counter()
-        s, cs, what, dwh, _ = orc.scale_update(X, O, W_O, wmax, p.gamma, np.ones(O.size, np.float32),
-                                               np.ones(p.c_in, np.float32))
-        Xq, dx, xo = orc.quant_act(X[:rows], cs, O)
-        orc.linear_fwd(Xq, dx, xo, Wq, dw, what, dwh, X[:rows], A if p.lora_rank else None,
-                       B if p.lora_rank else None, p.lora_scale)
-        ops = 2.0 * rows * p.c_out * (p.c_in + O.size)
-        if p.backward:
-            orc.linear_bwd_dx(dY[:rows], Wq, dw, A if p.lora_rank else None, B if p.lora_rank else None, p.lora_scale)
-            ops += 2.0 * rows * p.c_out * p.c_in
-        secs = time.perf_counter() - t0
+        orc.set_threads(min(orc.max_threads(), 16))
+        state = []
+        for L in layers:
+            p = L["p"]
+            W, O = synth.weight(p), synth.outlier_indices(p)
+            A, B = synth.lora(p)
+            Wq, dw = orc.weight_quantize(W)
+            W_O, wmax = orc.outlier_rows(W, O)
+            state.append(dict(p=p, O=O, A=A if p.lora_rank else None, B=B if p.lora_rank else None, Wq=Wq, dw=dw,
+                              W_O=W_O, wmax=wmax, s=np.ones(O.size, np.float32), cs=np.ones(p.c_in, np.float32)))
+        batches = [[(synth.activations(S["p"], b), synth.out_grad(S["p"], b) if S["p"].backward else None)
+                    for S in state] for b in range(min(args.batches, 2))]
+        secs, ops, nsteps = 0.0, 0.0, 0
+        while secs < 10.0 and nsteps < 8:
+            t0 = time.perf_counter()
+            for S, (X, dY) in zip(state, batches[nsteps % len(batches)]):
+                p = S["p"]
+                S["s"], S["cs"], what, dwh, _ = orc.scale_update(X, S["O"], S["W_O"], S["wmax"], p.gamma, S["s"],
+                                                                 S["cs"])
+                Xq, dx, xo = orc.quant_act(X, S["cs"], S["O"])
+                orc.linear_fwd(Xq, dx, xo, S["Wq"], S["dw"], what, dwh, X, S["A"], S["B"], p.lora_scale)
+                ops += 2.0 * p.t * p.c_out * (p.c_in + S["O"].size)
+                if p.backward:
+                    orc.linear_bwd_dx(dY, S["Wq"], S["dw"], S["A"], S["B"], p.lora_scale)
+                    ops += 2.0 * p.t * p.c_out * p.c_in
+            secs += time.perf_counter() - t0
+            nsteps += 1
         out["cpu_baseline"] = {"value": round(ops / secs / 1e12, 5), "unit": "TOPS", "cores": orc.max_threads(),
                                "kind": "oracle", "seconds": round(secs, 2),
-                               "sample": "%s projection, first %d of %d rows, one full step (scale update on all rows, "
-                                         "quantize, forward, dX)" % (p.name, rows, p.t)}
+                               "sample": "%d whole step(s) of the same workload (every projection, all %d rows: scale "
+                                         "update, quantize, forward, dX)" % (nsteps, layers[0]["p"].t)}
     print(json.dumps(out))
 
 

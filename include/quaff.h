@@ -177,6 +177,18 @@ int64_t quaff_profile_collect(void);
 int quaff_profile_launch(int64_t index, int* kind, float* ms);
 const char* quaff_profile_kind_name(int kind);
 
+/*
+ * Device micro-benchmarks for honest roofline denominators (not part of the method).  Unlike everything above
+ * these calls allocate device memory, run on the default stream and synchronize.
+ *   quaff_microbench_mfma_i8  sustained rate (TOP/s) and shader clock (MHz) of a register-only
+ *                             v_mfma_i32_32x32x32_i8 loop, two wavefronts per SIMD on every compute unit, with
+ *                             constant operands (random_operands = 0) or full-range random INT8 operands (1): the
+ *                             clock the chip sustains, and so the attainable MFMA rate, depends on operand toggling
+ *   quaff_microbench_copy     bandwidth (GB/s, bytes read + bytes written) of a streaming copy of `bytes` bytes
+ */
+int quaff_microbench_mfma_i8(int random_operands, double* tops, double* clock_mhz);
+int quaff_microbench_copy(size_t bytes, double* gbs_read_plus_write);
+
 #ifdef __cplusplus
 }
 #endif

@@ -37,6 +37,8 @@ SIGNATURES = {
     "quaff_profile_collect": (_i64, []),
     "quaff_profile_launch": (C.c_int, [_i64, C.POINTER(C.c_int), C.POINTER(C.c_float)]),
     "quaff_profile_kind_name": (C.c_char_p, [C.c_int]),
+    "quaff_microbench_mfma_i8": (C.c_int, [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+    "quaff_microbench_copy": (C.c_int, [_sz, C.POINTER(C.c_double)]),
 }
 
 _lib = None
@@ -167,3 +169,17 @@ def profile_launches():
         _check(lib().quaff_profile_launch(i, C.byref(kind), C.byref(ms)))
         out.append((lib().quaff_profile_kind_name(kind.value).decode(), float(ms.value)))
     return out
+
+
+def microbench_mfma_i8(random_operands: bool):
+    """(TOP/s, shader clock MHz) of a register-only INT8 MFMA loop on the whole chip."""
+    tops, mhz = C.c_double(), C.c_double()
+    _check(lib().quaff_microbench_mfma_i8(1 if random_operands else 0, C.byref(tops), C.byref(mhz)))
+    return tops.value, mhz.value
+
+
+def microbench_copy(nbytes: int = 1 << 30) -> float:
+    """GB/s (read + write) of a streaming device copy."""
+    gbs = C.c_double()
+    _check(lib().quaff_microbench_copy(nbytes, C.byref(gbs)))
+    return gbs.value

@@ -11,7 +11,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libquaff.so")
 
 SOURCES = ["quaff_api.cpp", "quaff_prepare.hip", "quaff_scale.hip", "quaff_quant.hip", "quaff_lora.hip",
-           "quaff_gemm.hip", "quaff_profile.cpp"]
+           "quaff_gemm.hip", "quaff_profile.cpp", "quaff_microbench.hip"]
 
 # -ffp-contract=off: the quantizer's fp32 operation sequence is part of the arithmetic contract (no fused
 # multiply-add unless written explicitly); correctly rounded fp32 divide and sqrt for the same reason.

@@ -90,6 +90,7 @@ __device__ __forceinline__ void gemm_mainloop_dma(const int8_t* __restrict__ gA,
 #ifdef QUAFF_GEMM_TIMING
     long long quaff_timing[2] = {0, 0};
     long long tstart_ = __builtin_amdgcn_s_memtime();
+    long long wstart_ = wall_clock64();
 #endif
     // prologue: fill the ring (tiles beyond the last are clamped to it: harmless rewrites of a free stage)
 #pragma unroll
@@ -145,7 +146,7 @@ __device__ __forceinline__ void gemm_mainloop_dma(const int8_t* __restrict__ gA,
     if ((threadIdx.x & 63) == 0 && blockIdx.x < 64) {
         long long tend_ = __builtin_amdgcn_s_memtime();
         long long* o = quaff_timing_out + (blockIdx.x * 8 + (threadIdx.x >> 6)) * 4;
-        o[0] = quaff_timing[0]; o[1] = quaff_timing[1]; o[2] = tend_ - tstart_; o[3] = KT;
+        o[0] = quaff_timing[0]; o[1] = wall_clock64() - wstart_; o[2] = tend_ - tstart_; o[3] = KT;
     }
 #endif
 }

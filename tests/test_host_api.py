@@ -1,0 +1,82 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every symbol the header declares, and
+rejects bad arguments with the documented status codes before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2505_14742_amd import binding as q
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "quaff.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(quaff_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = q.lib()
+    names = _declared_symbols()
+    assert len(names) >= 15
+    for n in names:
+        assert hasattr(lib, n), "missing export " + n
+    assert set(q.SIGNATURES) == set(names), "binding and header disagree: %s" % (set(q.SIGNATURES) ^ set(names))
+
+
+def test_status_strings_and_sizes():
+    lib = q.lib()
+    for code in (0, -1, -2, -3, -4, -5, -99):
+        assert lib.quaff_status_string(code)
+    assert q.padded_outliers(0) == 0 and q.padded_outliers(1) == 64 and q.padded_outliers(64) == 64
+    assert q.padded_outliers(65) == 128
+    assert q.packed_weight_bytes(3072, 9216) >= 2 * 3072 * 9216
+    assert q.packed_weight_bytes(0, 16) == 0
+    w0 = q.workspace_bytes(2048, 3072, 9216, 31, 16)
+    assert w0 >= 2048 * 9216 + 2048 * 4 + 2 * 2048 * 16 * 2          # backward: codes of dY, steps, T hi/lo
+    assert q.workspace_bytes(4096, 3072, 9216, 31, 16) > w0
+    assert q.workspace_bytes(0, 3072, 9216, 31, 16) == 0
+
+
+A16 = 0x1000    # a non-null, 16-byte aligned fake device address: argument checks come before any device access
+
+
+def test_argument_errors_are_reported_without_touching_the_device():
+    lib = q.lib()
+    # NULL pointers
+    assert lib.quaff_quant_act(None, 8, 64, 64, None, None, 0, A16, A16, None, None) == q.ERR_NULL
+    assert lib.quaff_linear_fwd_acc(None, None, 8, A16, 64, 64, None, 0, A16, None, None) == q.ERR_NULL
+    # shapes: t = 0, c not a multiple of 16, ldx < c, n_outlier > c
+    assert lib.quaff_quant_act(A16, 0, 64, 64, None, None, 0, A16, A16, None, None) == q.ERR_SHAPE
+    assert lib.quaff_quant_act(A16, 8, 72, 72, None, None, 0, A16, A16, None, None) == q.ERR_SHAPE
+    assert lib.quaff_quant_act(A16, 8, 64, 32, None, None, 0, A16, A16, None, None) == q.ERR_SHAPE
+    assert lib.quaff_quant_act(A16, 8, 64, 64, None, A16, 65, A16, A16, A16, None) == q.ERR_SHAPE
+    # alignment: pointer not 16-byte aligned, leading dimension not a multiple of 8
+    assert lib.quaff_quant_act(A16 + 2, 8, 64, 64, None, None, 0, A16, A16, None, None) == q.ERR_ALIGN
+    assert lib.quaff_quant_act(A16, 8, 64, 68, None, None, 0, A16, A16, None, None) == q.ERR_ALIGN
+    # workspace too small / missing
+    need = q.workspace_bytes(8, 64, 64, 4, 16)
+    args = [A16, 8, 64, A16, A16, 64, 64, A16, A16, 16, C.c_float(1.0), A16, 64]
+    assert lib.quaff_linear_bwd_dx(*args, A16, need // 4, None) == q.ERR_WORKSPACE
+    assert lib.quaff_linear_bwd_dx(*args, None, 0, None) == q.ERR_WORKSPACE
+    # LoRA rank must be 0 or a multiple of 16 up to 128
+    bad_rank = list(args)
+    bad_rank[9] = 24
+    assert lib.quaff_linear_bwd_dx(*bad_rank, A16, need, None) == q.ERR_SHAPE
+    # gamma outside [0, 1]
+    assert lib.quaff_scale_update(A16, 8, 64, 64, A16, 4, A16, A16, 64, C.c_float(1.5), A16, A16, A16, A16, None,
+                                  A16, 1 << 20, None) == q.ERR_SHAPE
+    # scale update with an empty outlier set is a legal no-op
+    assert lib.quaff_scale_update(None, 8, 64, 64, None, 0, None, None, 64, C.c_float(0.2), None, None, None, None,
+                                  None, None, 0, None) == q.OK
+    # prepare: workspace check
+    assert lib.quaff_prepare_weight(A16, 64, 64, 64, None, 0, A16, A16, None, None, None, A16, 16, None) \
+        == q.ERR_WORKSPACE
+
+
+def test_binding_raises_with_status_text():
+    with pytest.raises(q.QuaffError) as e:
+        q._check(q.ERR_ALIGN)
+    assert "ALIGN" in str(e.value)
