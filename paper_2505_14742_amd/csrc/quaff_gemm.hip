@@ -53,16 +53,46 @@ static hipError_t launch_dma(const GemmArgs& g, bool dump, hipStream_t stream) {
     return hipGetLastError();
 }
 
+namespace {
+// Tile shapes of the fast path.  `spc` = workgroups that fit on one compute unit at once (LDS and registers);
+// `ineff` = measured cost per MAC relative to the 256x256 shape on a large problem.
+struct TileChoice { int bm, bn, spc; double ineff; };
+constexpr TileChoice kChoices[4] = {
+    {256, 256, 1, 1.00},   // 8 wavefronts, 128x64 each
+    {256, 288, 1, 1.03},   // 12 wavefronts, 64x96 each: 2048 x 9216 outputs are exactly 256 such tiles
+    {256, 128, 2, 1.15},   // 8 wavefronts, 64x64 each
+    {128, 192, 2, 1.20},   // 4 wavefronts, 64x96 each: 2048 x 3072 outputs are exactly 256 such tiles
+};
+
+// Estimated time of a tile shape on 256 compute units: full rounds of spc tiles per unit, then the remainder at one
+// tile per unit per pass.  The shape that wastes the fewest compute-unit passes wins.
+int choose_tile(int64_t M, int64_t N) {
+    int best = 0;
+    double best_cost = -1.0;
+    for (int c = 0; c < 4; ++c) {
+        const TileChoice& t = kChoices[c];
+        int64_t tiles = ((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn);
+        int64_t slots = 256 * t.spc;
+        int64_t full = tiles / slots, rem = tiles % slots;
+        double passes = (double)full * t.spc + (double)((rem + 255) / 256);
+        double cost = passes * t.bm * t.bn * t.ineff;
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = c; }
+    }
+    return best;
+}
+}  // namespace
+
 hipError_t launch_gemm(const GemmArgs& g, bool dump_acc, hipStream_t stream) {
     ProfScope prof(K_GEMM, stream);
     const int64_t lim32 = (int64_t)1 << 32;
     const bool dma_ok = g.K % 64 == 0 && g.M * g.lda < lim32 && g.N * g.ldb < lim32;
     if (!dma_ok) return launch_generic<128, 128, 64, 2, 2>(g, dump_acc, stream);
-    // Largest tiles (least L2 -> LDS traffic per MAC) once they give every compute unit about two tiles; a half-width
-    // tile with two workgroups per compute unit otherwise, so that one workgroup's epilogue overlaps the other's MFMAs.
-    const int64_t big_tiles = ((g.M + 255) / 256) * ((g.N + 255) / 256);
-    if (big_tiles >= 448) return launch_dma<256, 256, 2, 4, 3, 1>(g, dump_acc, stream);
-    return launch_dma<256, 128, 4, 2, 3, 1>(g, dump_acc, stream);
+    switch (choose_tile(g.M, g.N)) {
+        case 0: return launch_dma<256, 256, 2, 4, 3, 1>(g, dump_acc, stream);
+        case 1: return launch_dma<256, 288, 4, 3, 3, 1>(g, dump_acc, stream);
+        case 2: return launch_dma<256, 128, 4, 2, 3, 1>(g, dump_acc, stream);
+        default: return launch_dma<128, 192, 2, 2, 4, 2>(g, dump_acc, stream);
+    }
 }
 
 }  // namespace quaff

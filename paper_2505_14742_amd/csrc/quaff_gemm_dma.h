@@ -23,11 +23,11 @@ struct DmaCfg {
     static constexpr int WM = BM / WGM, WN = BN / WGN;    // wavefront tile
     static constexpr int TM = WM / 32, TN = WN / 32;      // 32x32 MFMA blocks per wavefront tile
     static constexpr int A_BYTES = BM * BK, STAGE_BYTES = (BM + BN) * BK;
-    static constexpr int NLOAD = (BM + BN) / (16 * NW);   // direct loads per lane per stage (1 KiB per wavefront each)
-    static constexpr int NLOAD_A = BM / (16 * NW);
+    static constexpr int NGROUP = (BM + BN) / 16;         // 16-row groups per stage, one direct load (1 KiB) each
+    static constexpr int NLOAD = (NGROUP + NW - 1) / NW;  // direct loads per lane per stage
     static constexpr int STAGES_ = STAGES;
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
-    static_assert(BM % (16 * NW) == 0 && BN % (16 * NW) == 0, "every wavefront loads whole 16-row groups of A and of B");
+    static_assert(BM % 16 == 0 && BN % 16 == 0, "stages are filled in 16-row groups");
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wavefront tile is made of 32x32 blocks");
     static_assert(STAGES >= 3 && (STAGES - 2) * NLOAD < 64, "ring depth / vmcnt range");
 };
@@ -61,9 +61,12 @@ __device__ __forceinline__ void gemm_mainloop_dma(const int8_t* __restrict__ gA,
         const int64_t k0 = (int64_t)tile * C::BK;
 #pragma unroll
         for (int j = 0; j < NLOAD; ++j) {
-            const bool isA = j < C::NLOAD_A;
+            // group q of the stage: A rows first, then B rows.  A wavefront whose last slot falls past the end repeats
+            // its previous group (same bytes to the same place), so every wavefront issues NLOAD loads per stage
+            int q = j * C::NW + wave;
+            if (q >= C::NGROUP) q -= C::NW;
+            const bool isA = q < C::A_BYTES / 1024;
             const int8_t* src = (isA ? gA : gB) + k0 + voff[j];
-            const int q = isA ? j * C::NW + wave : C::A_BYTES / 1024 + (j - C::NLOAD_A) * C::NW + wave;
             lds_i8* dst = dma + stage * C::STAGE_BYTES + q * 1024;
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                              (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
@@ -173,8 +176,10 @@ gemm_i8_dma_kernel(const GemmArgs g, const TileMap tmap) {
         const int r = lane >> 2, chunk = (lane & 3) ^ ((lane >> 4) & 3);
 #pragma unroll
         for (int j = 0; j < C::NLOAD; ++j) {
-            const bool isA = j < C::NLOAD_A;
-            int local = ((isA ? j : j - C::NLOAD_A) * C::NW + wave) * 16 + r;
+            int q = j * C::NW + wave;
+            if (q >= C::NGROUP) q -= C::NW;
+            const bool isA = q < BM / 16;
+            int local = (isA ? q : q - BM / 16) * 16 + r;
             int64_t row = (isA ? m0 : n0) + local;
             int64_t lim = (isA ? g.M : g.N) - 1;
             row = row < lim ? row : lim;                        // clamp: rows past the edge are never stored
