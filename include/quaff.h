@@ -21,7 +21,7 @@
  *    call returns without synchronizing.  Nothing is printed.
  *  - Matrices are row-major.  bf16 values are passed as uint16_t bit patterns.
  *  - c_in and c_out must be multiples of 16; t >= 1; n_outlier >= 0; lora_rank is 0 or a multiple of 16
- *    (at most 128).  Data pointers must be 16-byte aligned and leading dimensions multiples of 8 elements.
+ *    (at most 64).  Data pointers must be 16-byte aligned and leading dimensions multiples of 8 elements.
  *  - O must be sorted, unique and inside [0, c_in): a documented precondition, not checked on the device.
  *    Non-finite inputs are outside the contract (no hang, no out-of-bounds access, values unspecified).
  *  - Return value: QUAFF_OK or a negative QUAFF_ERR_* code; nothing has been enqueued when an error is

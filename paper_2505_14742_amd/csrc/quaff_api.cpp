@@ -21,7 +21,7 @@ bool dims_ok(int64_t t, int64_t c_in, int64_t c_out) {
     return t >= 1 && t < lim && c_in >= 16 && c_out >= 16 && c_in < (1 << 20) && c_out < (1 << 20) &&
            c_in % 16 == 0 && c_out % 16 == 0;
 }
-bool rank_ok(int32_t r) { return r == 0 || (r > 0 && r <= 128 && r % 16 == 0); }
+bool rank_ok(int32_t r) { return r == 0 || (r > 0 && r <= 64 && r % 16 == 0); }
 
 struct PackedWeight {
     int8_t* Wt;   // [c_out x c_in]

@@ -17,7 +17,8 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kLoraWaves = 8;
+constexpr int kLoraWaves = 16;
+constexpr int kLoraUnroll = 6;   // contraction steps whose loads are issued together (latency hiding)
 
 __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
     uint32_t u = __float_as_uint(f);
@@ -55,38 +56,56 @@ lora_down_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx, 
 #pragma unroll
     for (int b = 0; b < R16; ++b) acc[b] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    for (int k0 = wave * 32; k0 < c; k0 += kLoraWaves * 32) {
-        const int k = k0 + g * 8;          // this lane's eight contraction indices
-        u32x4 xa = (u32x4){0, 0, 0, 0};
-        if (live && k < c) xa = *reinterpret_cast<const u32x4*>(xrow + k);
-        if (!L_RC) {
-            // stage L[k0 .. k0+32) x r transposed into this wavefront's LDS slice: lt[p][kk]
-            constexpr int VEC = 32 * r / 8;                 // 16-byte vectors in the slice
+    for (int kk0 = wave * 32; kk0 < c; kk0 += kLoraWaves * 32 * kLoraUnroll) {
+        u32x4 xa[kLoraUnroll], lb[kLoraUnroll][R16];
+        // all global loads of the batch first
 #pragma unroll
-            for (int v0 = 0; v0 < VEC; v0 += 64) {
-                int v = v0 + lane;
-                int kk = v / (r / 8), p0 = (v % (r / 8)) * 8;
-                u32x4 lv = (u32x4){0, 0, 0, 0};
-                if (v < VEC && k0 + kk < c) lv = *reinterpret_cast<const u32x4*>(L + (int64_t)(k0 + kk) * r + p0);
-                if (v < VEC) {
+        for (int u = 0; u < kLoraUnroll; ++u) {
+            const int k0 = kk0 + u * kLoraWaves * 32;
+            const int k = k0 + g * 8;          // this lane's eight contraction indices
+            xa[u] = (u32x4){0, 0, 0, 0};
+            if (live && k < c) xa[u] = *reinterpret_cast<const u32x4*>(xrow + k);
+            if (L_RC) {
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        lt[wave][p0 + 2 * u][kk] = (uint16_t)(lv[u] & 0xFFFFu);
-                        lt[wave][p0 + 2 * u + 1][kk] = (uint16_t)(lv[u] >> 16);
-                    }
+                for (int b = 0; b < R16; ++b) {
+                    lb[u][b] = (u32x4){0, 0, 0, 0};
+                    if (k < c) lb[u][b] = *reinterpret_cast<const u32x4*>(L + (int64_t)(b * 16 + m) * c + k);
                 }
+            } else {
+                // L[k0 .. k0+32) x r arrives as 16-byte vectors along r; kept in lb[u][*] until it is transposed
+                constexpr int VEC = 32 * r / 8;
+#pragma unroll
+                for (int b = 0; b < R16; ++b) {   // VEC = 64 * R16: one vector per lane per b
+                    int v = b * 64 + lane;
+                    int kk = v / (r / 8), p0 = (v % (r / 8)) * 8;
+                    lb[u][b] = (u32x4){0, 0, 0, 0};
+                    if (k0 + kk < c) lb[u][b] = *reinterpret_cast<const u32x4*>(L + (int64_t)(k0 + kk) * r + p0);
+                }
+                (void)VEC;
             }
         }
 #pragma unroll
-        for (int b = 0; b < R16; ++b) {
-            u32x4 lb = (u32x4){0, 0, 0, 0};
-            if (L_RC) {
-                if (k < c) lb = *reinterpret_cast<const u32x4*>(L + (int64_t)(b * 16 + m) * c + k);
-            } else {
-                lb = *reinterpret_cast<const u32x4*>(&lt[wave][b * 16 + m][g * 8]);
+        for (int u = 0; u < kLoraUnroll; ++u) {
+            if (!L_RC) {
+                // transpose this step's slice through the wavefront's LDS piece: lt[p][kk]
+#pragma unroll
+                for (int b = 0; b < R16; ++b) {
+                    int v = b * 64 + lane;
+                    int kk = v / (r / 8), p0 = (v % (r / 8)) * 8;
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) {
+                        lt[wave][p0 + 2 * w][kk] = (uint16_t)(lb[u][b][w] & 0xFFFFu);
+                        lt[wave][p0 + 2 * w + 1][kk] = (uint16_t)(lb[u][b][w] >> 16);
+                    }
+                }
+#pragma unroll
+                for (int b = 0; b < R16; ++b)
+                    lb[u][b] = *reinterpret_cast<const u32x4*>(&lt[wave][b * 16 + m][g * 8]);
             }
-            acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xa),
-                                                             __builtin_bit_cast(bf16x8, lb), acc[b], 0, 0, 0);
+#pragma unroll
+            for (int b = 0; b < R16; ++b)
+                acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xa[u]),
+                                                                 __builtin_bit_cast(bf16x8, lb[u][b]), acc[b], 0, 0, 0);
         }
     }
 #pragma unroll
@@ -121,7 +140,7 @@ static void dispatch(int R16, dim3 grid, hipStream_t stream, const uint16_t* X, 
                            scale, T_hi, T_lo, row_blocks, tr_src, tr_dst, tr_rows, tr_cols);                       \
         break;
     switch (R16) {
-        QUAFF_LORA(1) QUAFF_LORA(2) QUAFF_LORA(3) QUAFF_LORA(4) QUAFF_LORA(5) QUAFF_LORA(6) QUAFF_LORA(7) QUAFF_LORA(8)
+        QUAFF_LORA(1) QUAFF_LORA(2) QUAFF_LORA(3) QUAFF_LORA(4)
     }
 #undef QUAFF_LORA
 }

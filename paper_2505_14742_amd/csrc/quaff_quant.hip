@@ -78,6 +78,22 @@ quant_rows_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx,
         raw[i] = (u32x4){0, 0, 0, 0};
         if (live && col < c) raw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xrow + col));
     }
+    // the outlier columns' values are gathered now so that their (dependent) loads overlap the row loads
+    constexpr int GPL = 4;                       // gathered outliers per lane in registers (TPR * GPL per row)
+    float xo[GPL];
+    const bool gather_regs = xq_O && n_pad <= TPR * GPL;
+    if (gather_regs) {
+#pragma unroll
+        for (int u = 0; u < GPL; ++u) {
+            int k = lane + u * TPR;
+            xo[u] = 0.0f;
+            if (live && k < n) {
+                int col = O[k];
+                float x = bf16_bits_to_f32(xrow[col]);
+                xo[u] = cs ? __fmul_rn(x, cs[col]) : x;
+            }
+        }
+    }
     float m = 0.0f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
@@ -109,7 +125,16 @@ quant_rows_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx,
             *reinterpret_cast<u32x2*>(qrow + col) = pack_codes(v, cc);
         }
     }
-    if (xq_O) write_outlier_codes(xrow, cs, O, n, n_pad, cc, xq_O + row * (int64_t)n_pad, lane, TPR);
+    if (gather_regs) {
+        int8_t* dst = xq_O + row * (int64_t)n_pad;
+#pragma unroll
+        for (int u = 0; u < GPL; ++u) {
+            int k = lane + u * TPR;
+            if (k < n_pad) dst[k] = (int8_t)rtn_code(xo[u], cc);   // xo = 0 beyond n: code 0
+        }
+    } else if (xq_O) {
+        write_outlier_codes(xrow, cs, O, n, n_pad, cc, xq_O + row * (int64_t)n_pad, lane, TPR);
+    }
 }
 
 // Fallback for very long rows: one workgroup per row, two passes over the row.

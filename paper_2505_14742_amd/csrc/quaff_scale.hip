@@ -15,7 +15,8 @@
 namespace quaff {
 
 constexpr int kRowsPerSlab = 16;
-constexpr int kMaxSlabs = 256;
+constexpr int kMaxSlabs = 128;
+constexpr int kWhatThreads = 128;   // output channels per workgroup of momentum_what_kernel
 
 int scale_update_blocks(int64_t t) {
     int64_t b = (t + kRowsPerSlab - 1) / kRowsPerSlab;
@@ -34,20 +35,28 @@ colmax_outlier_kernel(const uint16_t* __restrict__ X, int64_t t, int64_t ldx, co
     __syncthreads();
     const int per_group = kRowsPerSlab * n;
     for (int64_t r0 = (int64_t)blockIdx.x * kRowsPerSlab; r0 < t; r0 += (int64_t)nslab * kRowsPerSlab) {
-        for (int e = threadIdx.x; e < per_group; e += 256) {
-            int r = e / n, k = e - r * n;
-            int64_t row = r0 + r;
-            if (row < t) {
-                uint32_t mag = ((uint32_t)X[row * ldx + O[k]] & 0x7FFFu) << 16;   // |x| as fp32 bits
-                atomicMax(&smax[k], mag);
+        for (int e0 = threadIdx.x; e0 < per_group; e0 += 4 * 256) {   // four independent gathers in flight per thread
+            uint32_t mag[4];
+            int kk[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                int e = e0 + u * 256;
+                int ec = e < per_group ? e : per_group - 1;
+                int r = ec / n;
+                kk[u] = ec - r * n;
+                int64_t row = r0 + r < t ? r0 + r : t - 1;
+                mag[u] = ((uint32_t)X[row * ldx + O[kk[u]]] & 0x7FFFu) << 16;   // |x| as fp32 bits
             }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (e0 + u * 256 < per_group) atomicMax(&smax[kk[u]], mag[u]);
         }
     }
     __syncthreads();
     for (int k = threadIdx.x; k < n; k += 256) part[(int64_t)blockIdx.x * n + k] = smax[k];
 }
 
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(kWhatThreads)
 momentum_what_kernel(const uint32_t* __restrict__ part, int nslab, int n, int n_pad, const float* __restrict__ wmax_O,
                      const float* __restrict__ s_prev, float gamma, const int32_t* __restrict__ O,
                      float* __restrict__ s_O, float* __restrict__ colscale, float* __restrict__ cmax_out,
@@ -55,46 +64,90 @@ momentum_what_kernel(const uint32_t* __restrict__ part, int nslab, int n, int n_
                      float* __restrict__ delta_what) {
     extern __shared__ float sm1[];                                  // [n] : s_k - 1
     uint32_t* smax = reinterpret_cast<uint32_t*>(sm1 + n);         // [n]
-    for (int k = threadIdx.x; k < n; k += 256) smax[k] = 0u;
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const int64_t j = (int64_t)blockIdx.x * kWhatThreads + threadIdx.x;
+    const int64_t jc = j < c_out ? j : c_out - 1;
+    const bool small = n <= 64;
+    // Every global load that does not depend on the reduction is issued first, so that the kernel pays about one
+    // memory round trip instead of three: this thread's column of W_O (n <= 64: kept in registers), its share of the
+    // partial maxima, and the per-outlier constants.
+    float w[64];
+    if (small) {
+#pragma unroll
+        for (int k = 0; k < 64; ++k) w[k] = W_O[(int64_t)(k < n ? k : n - 1) * c_out + jc];
+    }
+    const int kk = threadIdx.x < n ? threadIdx.x : n - 1;          // outlier handled by this thread (first pass)
+    const float wmax0 = wmax_O[kk], sprev0 = s_prev[kk];
+    const int o0 = O[kk];
+    for (int k = threadIdx.x; k < n; k += kWhatThreads) smax[k] = 0u;
     __syncthreads();
     const int total = nslab * n;
-    for (int e = threadIdx.x; e < total; e += 256) atomicMax(&smax[e % n], part[e]);
+    for (int e0 = threadIdx.x; e0 < total; e0 += 8 * kWhatThreads) {   // eight independent loads in flight per thread
+        uint32_t v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            int e = e0 + u * kWhatThreads;
+            v[u] = part[e < total ? e : total - 1];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            int e = e0 + u * kWhatThreads;
+            if (e < total) atomicMax(&smax[e % n], v[u]);
+        }
+    }
     __syncthreads();
-    for (int k = threadIdx.x; k < n; k += 256) {
+    for (int k = threadIdx.x; k < n; k += kWhatThreads) {
+        const bool first = k == (int)threadIdx.x;
         float cmax = __uint_as_float(smax[k]);
         float beta = 1.0f;
-        float wmax = wmax_O[k];
+        float wmax = first ? wmax0 : wmax_O[k];
         if (wmax > 0.0f) beta = fmaxf(1.0f, __builtin_sqrtf(__fdiv_rn(cmax, wmax)));                 // Eq. 8
-        float s = __fadd_rn(__fmul_rn(gamma, s_prev[k]), __fmul_rn(__fsub_rn(1.0f, gamma), beta));   // Eq. 7
+        float sp = first ? sprev0 : s_prev[k];
+        float s = __fadd_rn(__fmul_rn(gamma, sp), __fmul_rn(__fsub_rn(1.0f, gamma), beta));         // Eq. 7
         sm1[k] = __fsub_rn(s, 1.0f);
         if (blockIdx.x == 0) {
             s_O[k] = s;
-            colscale[O[k]] = __fdiv_rn(1.0f, s);
+            colscale[first ? o0 : O[k]] = __fdiv_rn(1.0f, s);
             if (cmax_out) cmax_out[k] = cmax;
         }
     }
     __syncthreads();
-    int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (j >= c_out) return;
-    float m = 0.0f;
-    for (int k = 0; k < n; ++k) m = fmaxf(m, fabsf(__fmul_rn(sm1[k], W_O[(int64_t)k * c_out + j])));
-    float d, c;
-    rtn_steps(m, d, c);
-    delta_what[j] = d;
-    // row j of what_int holds n_pad codes; written sixteen at a time
-    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    // what[k, j] for this output channel (Eq. 5), quantized per output channel (Eq. 1)
     u32x4* dst = reinterpret_cast<u32x4*>(what_int + j * n_pad);
-    for (int k16 = 0; k16 < n_pad; k16 += 16) {
-        u32x4 w = (u32x4){0, 0, 0, 0};
+    float d, c;
+    if (small) {
+        float m = 0.0f;
 #pragma unroll
-        for (int u = 0; u < 16; ++u) {
-            int k = k16 + u;
-            int q = 0;
-            if (k < n) q = rtn_code(__fmul_rn(sm1[k], W_O[(int64_t)k * c_out + j]), c);
-            w[u >> 2] |= (uint32_t)(q & 0xFF) << (8 * (u & 3));
+        for (int k = 0; k < 64; ++k) {
+            w[k] = k < n ? __fmul_rn(sm1[k < n ? k : n - 1], w[k]) : 0.0f;
+            m = fmaxf(m, fabsf(w[k]));
         }
-        dst[k16 >> 4] = w;
+        rtn_steps(m, d, c);
+#pragma unroll
+        for (int k16 = 0; k16 < 64; k16 += 16) {
+            u32x4 q4 = (u32x4){0, 0, 0, 0};
+#pragma unroll
+            for (int u = 0; u < 16; ++u) q4[u >> 2] |= (uint32_t)(rtn_code(w[k16 + u], c) & 0xFF) << (8 * (u & 3));
+            dst[k16 >> 4] = q4;
+        }
+    } else {
+        float m = 0.0f;
+        for (int k = 0; k < n; ++k) m = fmaxf(m, fabsf(__fmul_rn(sm1[k], W_O[(int64_t)k * c_out + j])));
+        rtn_steps(m, d, c);
+        for (int k16 = 0; k16 < n_pad; k16 += 16) {
+            u32x4 q4 = (u32x4){0, 0, 0, 0};
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                int k = k16 + u;
+                int q = 0;
+                if (k < n) q = rtn_code(__fmul_rn(sm1[k], W_O[(int64_t)k * c_out + j]), c);
+                q4[u >> 2] |= (uint32_t)(q & 0xFF) << (8 * (u & 3));
+            }
+            dst[k16 >> 4] = q4;
+        }
     }
+    delta_what[j] = d;
 }
 
 hipError_t launch_scale_update(const uint16_t* X, int64_t t, int64_t c_in, int64_t ldx, const int32_t* O, int32_t n,
@@ -112,7 +165,7 @@ hipError_t launch_scale_update(const uint16_t* X, int64_t t, int64_t c_in, int64
                            n, part, s_O, s_prev);
     }
     ProfScope prof(K_MOMENTUM, stream);
-    hipLaunchKernelGGL(momentum_what_kernel, dim3((unsigned)((c_out + 255) / 256)), dim3(256),
+    hipLaunchKernelGGL(momentum_what_kernel, dim3((unsigned)((c_out + kWhatThreads - 1) / kWhatThreads)), dim3(kWhatThreads),
                        2 * n * sizeof(float), stream, part, nslab, n, n_pad, wmax_O, s_prev, gamma, O, s_O, colscale,
                        cmax_out, W_O, c_out, what_int, delta_what);
     return hipGetLastError();

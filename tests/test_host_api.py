@@ -61,7 +61,7 @@ def test_argument_errors_are_reported_without_touching_the_device():
     args = [A16, 8, 64, A16, A16, 64, 64, A16, A16, 16, C.c_float(1.0), A16, 64]
     assert lib.quaff_linear_bwd_dx(*args, A16, need // 4, None) == q.ERR_WORKSPACE
     assert lib.quaff_linear_bwd_dx(*args, None, 0, None) == q.ERR_WORKSPACE
-    # LoRA rank must be 0 or a multiple of 16 up to 128
+    # LoRA rank must be 0 or a multiple of 16 up to 64
     bad_rank = list(args)
     bad_rank[9] = 24
     assert lib.quaff_linear_bwd_dx(*bad_rank, A16, need, None) == q.ERR_SHAPE
