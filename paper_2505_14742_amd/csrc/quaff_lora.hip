@@ -63,14 +63,15 @@ lora_down_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx, 
         for (int u = 0; u < kLoraUnroll; ++u) {
             const int k0 = kk0 + u * kLoraWaves * 32;
             const int k = k0 + g * 8;          // this lane's eight contraction indices
-            xa[u] = (u32x4){0, 0, 0, 0};
-            if (live && k < c) xa[u] = *reinterpret_cast<const u32x4*>(xrow + k);
+            // loads are unconditional (address clamped into the row) so that the whole batch is in flight together;
+            // a step past the end contributes zero because its x fragment is cleared
+            const int kc = k < c ? k : c - 8;
+            xa[u] = *reinterpret_cast<const u32x4*>(xrow + kc);
+            if (!(live && k < c)) xa[u] = (u32x4){0, 0, 0, 0};
             if (L_RC) {
 #pragma unroll
-                for (int b = 0; b < R16; ++b) {
-                    lb[u][b] = (u32x4){0, 0, 0, 0};
-                    if (k < c) lb[u][b] = *reinterpret_cast<const u32x4*>(L + (int64_t)(b * 16 + m) * c + k);
-                }
+                for (int b = 0; b < R16; ++b)
+                    lb[u][b] = *reinterpret_cast<const u32x4*>(L + (int64_t)(b * 16 + m) * c + kc);
             } else {
                 // L[k0 .. k0+32) x r arrives as 16-byte vectors along r; kept in lb[u][*] until it is transposed
                 constexpr int VEC = 32 * r / 8;
@@ -78,8 +79,8 @@ lora_down_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx, 
                 for (int b = 0; b < R16; ++b) {   // VEC = 64 * R16: one vector per lane per b
                     int v = b * 64 + lane;
                     int kk = v / (r / 8), p0 = (v % (r / 8)) * 8;
-                    lb[u][b] = (u32x4){0, 0, 0, 0};
-                    if (k0 + kk < c) lb[u][b] = *reinterpret_cast<const u32x4*>(L + (int64_t)(k0 + kk) * r + p0);
+                    const int kr = k0 + kk < c ? k0 + kk : c - 1;
+                    lb[u][b] = *reinterpret_cast<const u32x4*>(L + (int64_t)kr * r + p0);
                 }
                 (void)VEC;
             }
