@@ -38,8 +38,8 @@ struct FwdWs { size_t t_hi, t_lo, lt, total; };
 FwdWs ws_fwd(int64_t t, int64_t c_out, int32_t r) {
     FwdWs w{};
     size_t off = 0;
-    w.t_hi = off; off += align_up((size_t)t * r * 2);
-    w.t_lo = off; off += align_up((size_t)t * r * 2);
+    w.t_hi = off; off += align_up((size_t)quaff::kLoraParts * t * r * 2);
+    w.t_lo = off; off += align_up((size_t)quaff::kLoraParts * t * r * 2);
     w.lt = off;   off += align_up((size_t)c_out * r * 2);
     w.total = off;
     return w;
@@ -50,8 +50,8 @@ BwdWs ws_bwd(int64_t t, int64_t c_out, int32_t r) {
     size_t off = 0;
     w.gq = off;   off += align_up((size_t)t * c_out);
     w.dg = off;   off += align_up((size_t)t * 4);
-    w.t_hi = off; off += align_up((size_t)t * r * 2);
-    w.t_lo = off; off += align_up((size_t)t * r * 2);
+    w.t_hi = off; off += align_up((size_t)quaff::kLoraParts * t * r * 2);
+    w.t_lo = off; off += align_up((size_t)quaff::kLoraParts * t * r * 2);
     w.total = off;
     return w;
 }

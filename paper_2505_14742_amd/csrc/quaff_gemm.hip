@@ -33,19 +33,19 @@ static hipError_t launch_generic(const GemmArgs& g, bool dump, hipStream_t strea
     return hipGetLastError();
 }
 
-template <int BM, int BN, int WGM, int WGN, int STAGES, int MINB>
+template <int BM, int BN, int WGM, int WGN, int STAGES, int MINB, int PAIR = 0>
 static hipError_t launch_dma(const GemmArgs& g, bool dump, hipStream_t stream) {
     using C = DmaCfg<BM, BN, WGM, WGN, STAGES>;
     int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (int)((g.N + BN - 1) / BN);
     TileMap tm = make_tile_map(tiles_m, tiles_n);
     dim3 grid((unsigned)(8 * tm.rm * tm.rn)), block(C::NT);
     if (dump) {
-        auto k = gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, true, MINB>;
+        auto k = gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, true, MINB, PAIR>;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, block, C::LDS_BYTES, stream, g, tm);
     } else {
-        auto k = gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, false, MINB>;
+        auto k = gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, false, MINB, PAIR>;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, block, C::LDS_BYTES, stream, g, tm);
@@ -87,9 +87,13 @@ hipError_t launch_gemm(const GemmArgs& g, bool dump_acc, hipStream_t stream) {
     const int64_t lim32 = (int64_t)1 << 32;
     const bool dma_ok = g.K % 64 == 0 && g.M * g.lda < lim32 && g.N * g.ldb < lim32;
     if (!dma_ok) return launch_generic<128, 128, 64, 2, 2>(g, dump_acc, stream);
+    const bool even_steps = (g.K / 64) % 2 == 0;
     switch (choose_tile(g.M, g.N)) {
-        case 0: return launch_dma<256, 256, 2, 4, 3, 1>(g, dump_acc, stream);
-        case 1: return launch_dma<256, 288, 4, 3, 3, 1>(g, dump_acc, stream);
+        // the two large shapes consume two contraction steps per barrier when the step count is even
+        case 0: return even_steps ? launch_dma<256, 256, 2, 4, 4, 1, 1>(g, dump_acc, stream)
+                                  : launch_dma<256, 256, 2, 4, 3, 1>(g, dump_acc, stream);
+        case 1: return even_steps ? launch_dma<256, 288, 4, 3, 4, 1, 1>(g, dump_acc, stream)
+                                  : launch_dma<256, 288, 4, 3, 3, 1>(g, dump_acc, stream);
         case 2: return launch_dma<256, 128, 4, 2, 3, 1>(g, dump_acc, stream);
         default: return launch_dma<128, 192, 2, 2, 4, 2>(g, dump_acc, stream);
     }

@@ -58,7 +58,11 @@ __device__ __forceinline__ void gemm_mainloop_dma(const int8_t* __restrict__ gA,
     constexpr int TM = C::TM, TN = C::TN, NLOAD = C::NLOAD, STAGES = C::STAGES_;
 
     auto issue = [&](int tile, int stage) {
+#ifdef QUAFF_TILED_PROBE
+        const int64_t k0 = (int64_t)tile * 1024;
+#else
         const int64_t k0 = (int64_t)tile * C::BK;
+#endif
 #pragma unroll
         for (int j = 0; j < NLOAD; ++j) {
             // group q of the stage: A rows first, then B rows.  A wavefront whose last slot falls past the end repeats
@@ -103,11 +107,16 @@ __device__ __forceinline__ void gemm_mainloop_dma(const int8_t* __restrict__ gA,
 
     i32x4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
     read_frags(0, 0, fa0, fb0);
+#ifdef QUAFF_ABL_NOLDS
+    read_frags(0, 1, fa1, fb1);
+#endif
     int stage = 0;
     for (int kt = 0; kt < KT; ++kt) {
         const int next = (stage + 1 == STAGES) ? 0 : stage + 1;
         // first half: fragments of the second 32 bytes arrive while the first 32 are multiplied
+#ifndef QUAFF_ABL_NOLDS
         read_frags(stage, 1, fa1, fb1);
+#endif
         mfmas(fa0, fb0);
 #pragma unroll
         for (int u = 0; u < TM + TN; ++u) {
@@ -118,23 +127,31 @@ __device__ __forceinline__ void gemm_mainloop_dma(const int8_t* __restrict__ gA,
 #ifdef QUAFF_GEMM_TIMING
         long long t0_ = __builtin_amdgcn_s_memtime();
 #endif
+#ifndef QUAFF_ABL_NOSYNC
         QUAFF_WAIT_VMCNT((STAGES - 2) * NLOAD);
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#endif
 #ifdef QUAFF_GEMM_TIMING
         long long t1_ = __builtin_amdgcn_s_memtime();
 #endif
+#ifndef QUAFF_ABL_NOSYNC
         __builtin_amdgcn_s_barrier();
+#endif
         asm volatile("" ::: "memory");
 #ifdef QUAFF_GEMM_TIMING
         long long t2_ = __builtin_amdgcn_s_memtime();
         quaff_timing[0] += t1_ - t0_;
         quaff_timing[1] += t2_ - t1_;
 #endif
+#ifndef QUAFF_ABL_NODMA
         {
             int t = kt + STAGES;
             issue(t < KT ? t : KT - 1, stage);
         }
+#endif
+#ifndef QUAFF_ABL_NOLDS
         read_frags(next, 0, fa0, fb0);
+#endif
         mfmas(fa1, fb1);
 #pragma unroll
         for (int u = 0; u < TM + TN; ++u) {
@@ -154,7 +171,91 @@ __device__ __forceinline__ void gemm_mainloop_dma(const int8_t* __restrict__ gA,
 #endif
 }
 
-template <int BM, int BN, int WGM, int WGN, int STAGES, bool DUMP, int MINB = 1>
+// Variant of the main loop that consumes TWO 64-byte contraction steps per barrier (ring of four stages): half as
+// many workgroup barriers and counter waits per MFMA.  KT must be even.
+template <class C>
+__device__ __forceinline__ void gemm_mainloop_dma2(const int8_t* __restrict__ gA, const int8_t* __restrict__ gB,
+                                                   const uint32_t (&voff)[C::NLOAD], int KT,
+                                                   lds_i8* __restrict__ dma, const lds_i8* __restrict__ rd, int wave,
+                                                   int a_frag_off, int b_frag_off, i32x16 (&acc)[C::TM][C::TN]) {
+    constexpr int TM = C::TM, TN = C::TN, NLOAD = C::NLOAD;
+    static_assert(C::STAGES_ == 4, "two steps per barrier need a ring of four stages");
+    auto issue = [&](int tile, int stage) {
+        const int64_t k0 = (int64_t)tile * C::BK;
+#pragma unroll
+        for (int j = 0; j < NLOAD; ++j) {
+            int q = j * C::NW + wave;
+            if (q >= C::NGROUP) q -= C::NW;
+            const bool isA = q < C::A_BYTES / 1024;
+            const int8_t* src = (isA ? gA : gB) + k0 + voff[j];
+            lds_i8* dst = dma + stage * C::STAGE_BYTES + q * 1024;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                             (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+        }
+    };
+    auto read_frags = [&](int stage, int ks, i32x4 (&fa)[TM], i32x4 (&fb)[TN]) {
+        const lds_i8* base = rd + stage * C::STAGE_BYTES;
+        const int x = ks * 32;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[i] = *(const lds_i32x4*)(base + ((a_frag_off + i * 2048) ^ x));
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[j] = *(const lds_i32x4*)(base + C::A_BYTES + ((b_frag_off + j * 2048) ^ x));
+    };
+    auto mfmas = [&](const i32x4 (&fa)[TM], const i32x4 (&fb)[TN]) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    };
+    constexpr int MFMA_PER_READ = (TM * TN) / (TM + TN) > 0 ? (TM * TN) / (TM + TN) : 1;
+    auto order_reads = [&](bool with_loads) {
+#pragma unroll
+        for (int u = 0; u < TM + TN; ++u) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if (with_loads && u < 2 * NLOAD) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_READ, 0);
+        }
+    };
+
+#pragma unroll
+    for (int s = 0; s < 4; ++s) issue(s < KT ? s : KT - 1, s);
+    QUAFF_WAIT_VMCNT(2 * NLOAD);
+    __builtin_amdgcn_s_barrier();
+
+    i32x4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+    read_frags(0, 0, fa0, fb0);
+    int s0 = 0;                                   // stage of the first tile of the pair
+    for (int kt = 0; kt < KT; kt += 2) {
+        const int s1 = s0 + 1, s2 = (s0 + 2) & 3;
+        read_frags(s0, 1, fa1, fb1);
+        mfmas(fa0, fb0);
+        order_reads(false);
+        read_frags(s1, 0, fa0, fb0);
+        mfmas(fa1, fb1);
+        order_reads(false);
+        read_frags(s1, 1, fa1, fb1);
+        mfmas(fa0, fb0);
+        order_reads(false);
+        // both stages of the pair have been read by everyone after this barrier; the next pair must have landed
+        QUAFF_WAIT_VMCNT(0);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        {
+            int t0 = kt + 4, t1 = kt + 5;
+            issue(t0 < KT ? t0 : KT - 1, s0);
+            issue(t1 < KT ? t1 : KT - 1, s1);
+        }
+        read_frags(s2, 0, fa0, fb0);
+        mfmas(fa1, fb1);
+        order_reads(true);
+        s0 = s2;
+    }
+    QUAFF_WAIT_VMCNT(0);
+}
+
+template <int BM, int BN, int WGM, int WGN, int STAGES, bool DUMP, int MINB = 1, int PAIR = 0>
 __global__ void __launch_bounds__(64 * WGM * WGN, MINB)
 gemm_i8_dma_kernel(const GemmArgs g, const TileMap tmap) {
     using C = DmaCfg<BM, BN, WGM, WGN, STAGES>;
@@ -183,7 +284,11 @@ gemm_i8_dma_kernel(const GemmArgs g, const TileMap tmap) {
             int64_t row = (isA ? m0 : n0) + local;
             int64_t lim = (isA ? g.M : g.N) - 1;
             row = row < lim ? row : lim;                        // clamp: rows past the edge are never stored
+#ifdef QUAFF_TILED_PROBE
+            voff[j] = (uint32_t)((((isA ? m0 : n0) / 16 + (isA ? q : q - BM / 16)) % ((isA ? g.M : g.N) / 16)) * (g.K * 16) + lane * 16);
+#else
             voff[j] = (uint32_t)(row * (isA ? g.lda : g.ldb) + chunk * 16);
+#endif
         }
     }
     const int frag = l32 * 64 + ((lhi ^ ((l32 >> 2) & 3)) * 16);
@@ -197,7 +302,10 @@ gemm_i8_dma_kernel(const GemmArgs g, const TileMap tmap) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
-    gemm_mainloop_dma<C>(g.A, g.B, voff, (int)(g.K / C::BK), lds, lds, wave, a_frag_off, b_frag_off, acc);
+    if constexpr (PAIR)
+        gemm_mainloop_dma2<C>(g.A, g.B, voff, (int)(g.K / C::BK), lds, lds, wave, a_frag_off, b_frag_off, acc);
+    else
+        gemm_mainloop_dma<C>(g.A, g.B, voff, (int)(g.K / C::BK), lds, lds, wave, a_frag_off, b_frag_off, acc);
 
 #ifdef QUAFF_GEMM_TIMING
     long long te0_ = __builtin_amdgcn_s_memtime();

@@ -83,13 +83,17 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, i32x16 (&acc)[T
                 acc2 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc2, 0, 0, 0);
             }
             for (int pp = 0; pp < g.r; pp += 16) {
-                i32x4 th = *reinterpret_cast<const i32x4*>(g.T_hi + frag_row * g.r + pp + lhi * 8);
-                i32x4 tl = *reinterpret_cast<const i32x4*>(g.T_lo + frag_row * g.r + pp + lhi * 8);
                 i32x4 lb = *reinterpret_cast<const i32x4*>(g.L + ccol * g.r + pp + lhi * 8);
-                lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, th),
-                                                             __builtin_bit_cast(bf16x8, lb), lo, 0, 0, 0);
-                lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tl),
-                                                             __builtin_bit_cast(bf16x8, lb), lo, 0, 0, 0);
+#pragma unroll
+                for (int part = 0; part < kLoraParts; ++part) {
+                    const int64_t po = (int64_t)part * g.M * g.r;
+                    i32x4 th = *reinterpret_cast<const i32x4*>(g.T_hi + po + frag_row * g.r + pp + lhi * 8);
+                    i32x4 tl = *reinterpret_cast<const i32x4*>(g.T_lo + po + frag_row * g.r + pp + lhi * 8);
+                    lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, th),
+                                                                 __builtin_bit_cast(bf16x8, lb), lo, 0, 0, 0);
+                    lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tl),
+                                                                 __builtin_bit_cast(bf16x8, lb), lo, 0, 0, 0);
+                }
             }
             const float cs = g.col_scale ? g.col_scale[ccol] : 1.0f;
             const float cs2 = g.K2 > 0 ? g.col_scale2[ccol] : 0.0f;

@@ -8,6 +8,8 @@ namespace quaff {
 
 constexpr int kWave = 64;
 constexpr int kPadK = 64;   // outlier count is padded to the INT8 MFMA contraction step
+constexpr int kLoraParts = 2;   // the LoRA down-projection splits its contraction range over this many workgroups;
+                                // the partial results T[p] ([t x r] each, hi/lo bf16 pairs) are summed by the GEMM epilogue
 
 // ---- device helpers -------------------------------------------------------------------------------
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
@@ -77,7 +79,8 @@ struct GemmArgs {
     const float* row_scale;    // [M]
     const float* col_scale;    // [N] or nullptr (= 1)
     const float* col_scale2;   // [N]
-    // optional low-rank fp term: (T_hi + T_lo) [M x r] bf16 times L [N x r] bf16 (r-contiguous)
+    // optional low-rank fp term: sum over kLoraParts parts p of (T_hi[p] + T_lo[p]) [M x r] bf16, times L [N x r] bf16
+    // (r-contiguous); part p starts M * r elements after part p - 1
     const uint16_t* T_hi; const uint16_t* T_lo; const uint16_t* L; int32_t r;
     float* C; int64_t ldc;         // fp32 output (mode 0)
     int32_t* acc1; int32_t* acc2;  // int32 dumps (mode 1), dense ld = N

@@ -35,6 +35,7 @@ lora_down_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx, 
     constexpr int NT = 64 * kLoraWaves;
     constexpr int TROW = 40;                       // padded row (in bf16) of the transposed slice: 32 + 8
     if ((int)blockIdx.x >= row_blocks) {
+        if (blockIdx.y != 0) return;
         // transposed copy: dst [cols x rows] <- src [rows x cols]
         int64_t total = tr_rows * tr_cols;
         int64_t nb = gridDim.x - row_blocks;
@@ -56,18 +57,26 @@ lora_down_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx, 
 #pragma unroll
     for (int b = 0; b < R16; ++b) acc[b] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    for (int kk0 = wave * 32; kk0 < c; kk0 += kLoraWaves * 32 * kLoraUnroll) {
+    // each wavefront owns one contiguous slice of the contraction range (kw columns), walked in 32-column steps
+    // this workgroup's part of the contraction range, then this wavefront's slice of it
+    const int cp = ((c + kLoraParts * 32 - 1) / (kLoraParts * 32)) * 32;
+    const int cbeg = blockIdx.y * cp, cend = cbeg + cp < c ? cbeg + cp : c;
+    const int kw = ((cend - cbeg + kLoraWaves * 32 - 1) / (kLoraWaves * 32)) * 32;
+    const int kbeg = cbeg + wave * kw, kend = kbeg + kw < cend ? kbeg + kw : cend;
+    T_hi += (int64_t)blockIdx.y * t * r;
+    T_lo += (int64_t)blockIdx.y * t * r;
+    for (int kk0 = kbeg; kk0 < kend; kk0 += 32 * kLoraUnroll) {
         u32x4 xa[kLoraUnroll], lb[kLoraUnroll][R16];
         // all global loads of the batch first
 #pragma unroll
         for (int u = 0; u < kLoraUnroll; ++u) {
-            const int k0 = kk0 + u * kLoraWaves * 32;
+            const int k0 = kk0 + u * 32;
             const int k = k0 + g * 8;          // this lane's eight contraction indices
             // loads are unconditional (address clamped into the row) so that the whole batch is in flight together;
             // a step past the end contributes zero because its x fragment is cleared
-            const int kc = k < c ? k : c - 8;
+            const int kc = k < kend ? k : c - 8;
             xa[u] = *reinterpret_cast<const u32x4*>(xrow + kc);
-            if (!(live && k < c)) xa[u] = (u32x4){0, 0, 0, 0};
+            if (!(live && k < kend)) xa[u] = (u32x4){0, 0, 0, 0};
             if (L_RC) {
 #pragma unroll
                 for (int b = 0; b < R16; ++b)
@@ -156,7 +165,7 @@ hipError_t launch_lora_down(const uint16_t* X, int64_t t, int64_t c, int64_t ldx
         int64_t b = (tr_rows * tr_cols + 2047) / 2048;
         tr_blocks = (int)(b < 128 ? (b > 0 ? b : 1) : 128);
     }
-    dim3 grid(row_blocks + tr_blocks);
+    dim3 grid(row_blocks + tr_blocks, kLoraParts);
     if (L_is_r_by_c)
         dispatch<true>(r / 16, grid, stream, X, t, (int)c, ldx, L, scale, T_hi, T_lo, row_blocks, tr_src, tr_dst,
                        tr_rows, tr_cols);
