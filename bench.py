@@ -154,6 +154,20 @@ def main():
     gemm_shapes = {nm: {"avg_us": round(st[0] / st[1] * 1e3, 2), "tops": round(st[2] / (st[0] / st[1] * 1e-3) / 1e12, 1),
                         "frac_peak": round(st[2] / (st[0] / st[1] * 1e-3) / 1e12 / INT8_PEAK_TOPS, 4)}
                    for nm, st in shape_stats.items()}
+    # HBM traffic of the GEMM launches: operands once, output once (algorithmic), against the PMC figure recorded
+    # for this workload (counters cannot be read from inside the process)
+    gemm_bytes = 0.0
+    for L in layers:
+        p = L["p"]
+        gemm_bytes += p.t * p.c_in + p.c_in * p.c_out + (p.t + p.c_out) * L["n_pad"] + 4.0 * p.t * p.c_out
+        if p.backward:
+            gemm_bytes += p.t * p.c_out + p.c_in * p.c_out + 4.0 * p.t * p.c_in
+    gemm_traffic = None
+    prof_file = os.path.join(ROOT, "profiles", "gemm_i8_hbm_traffic_phi3_attention.md")
+    if args.config == 2 and os.path.exists(prof_file):
+        for ln in open(prof_file):
+            if ln.strip().startswith("gemm_traffic_bytes_per_launch"):
+                gemm_traffic = int(ln.split("=")[1])
     # HBM-bound kernels: algorithmic bytes / measured time
     quant_bytes = 0.0
     for L in layers:
@@ -188,7 +202,9 @@ def main():
         "wall_ms_per_step": round(wall_ms / args.steps, 5),
         "roofline": {"bound": "mfma", "kernel": "gemm_i8 (all launches of the step)", "achieved": round(gemm_tops, 2),
                      "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": round(gemm_tops / INT8_PEAK_TOPS, 4),
-                     "traffic": None, "per_shape": gemm_shapes},
+                     "traffic": gemm_traffic, "traffic_unit": "bytes per GEMM launch (rocprofv3 FETCH_SIZE + "
+                     "WRITE_SIZE, scaled by the copy kernel; profiles/gemm_i8_hbm_traffic_phi3_attention.md)",
+                     "algorithmic_bytes_per_launch": round(gemm_bytes / len(order)), "per_shape": gemm_shapes},
         "kernels": kernels,
     }
 
