@@ -44,8 +44,15 @@ static hipError_t launch_dma(const GemmArgs& g, bool dump, hipStream_t stream) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, block, C::LDS_BYTES, stream, g, tm);
+    } else if ((int64_t)(g.K2 / 64) * C::K2_PLANES_BYTES <= C::EPI_LIMIT) {
+        // the epilogue operands are staged through the idle LDS ring
+        auto k = gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, false, MINB, PAIR, true>;
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_ALLOC);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(k, grid, block, C::LDS_ALLOC, stream, g, tm);
     } else {
-        auto k = gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, false, MINB, PAIR>;
+        // very wide second product: epilogue operands come straight from global memory
+        auto k = gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, false, MINB, PAIR, false>;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, block, C::LDS_BYTES, stream, g, tm);

@@ -7,18 +7,18 @@
 
 namespace quaff {
 
-#ifdef QUAFF_GEMM_TIMING
-__device__ long long quaff_timing_out[64 * 8 * 4];
-#endif
 typedef __attribute__((address_space(3))) int8_t lds_i8;
 typedef __attribute__((address_space(3))) i32x4 lds_i32x4;
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) f32x4 lds_f32x4;
+typedef __attribute__((address_space(3))) float lds_f32;
 
 // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt = [3:0] and [15:14])
 #define QUAFF_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 
 template <int BM, int BN, int WGM, int WGN, int STAGES>
 struct DmaCfg {
-    static constexpr int BK = 64;
+    static constexpr int BK = 64, BM_ = BM, BN_ = BN;
     static constexpr int NW = WGM * WGN, NT = 64 * NW;    // wavefronts / threads per workgroup
     static constexpr int WM = BM / WGM, WN = BN / WGN;    // wavefront tile
     static constexpr int TM = WM / 32, TN = WN / 32;      // 32x32 MFMA blocks per wavefront tile
@@ -27,9 +27,15 @@ struct DmaCfg {
     static constexpr int NLOAD = (NGROUP + NW - 1) / NW;  // direct loads per lane per stage
     static constexpr int STAGES_ = STAGES;
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
-    static_assert(BM % 16 == 0 && BN % 16 == 0, "stages are filled in 16-row groups");
-    static_assert(WM % 32 == 0 && WN % 32 == 0, "wavefront tile is made of 32x32 blocks");
-    static_assert(STAGES >= 3 && (STAGES - 2) * NLOAD < 64, "ring depth / vmcnt range");
+    // epilogue staging (gemm_epilogue_staged): one 64-byte-per-row plane per int8 / bf16 operand below EPI_LIMIT,
+    // the fp32 row and column scales in the last SCALE_BYTES of the allocation
+    static constexpr int K2_PLANES_BYTES = (BM + BN) * 64;                    // A2 and B2, 64 contraction bytes
+    static constexpr int LORA_PLANES_BYTES = (2 * kLoraParts * BM + BN) * 64; // T hi/lo of every part and L, 32 columns
+    static constexpr int BN_PAD = (BN + 63) / 64 * 64;
+    static constexpr int SCALE_BYTES = ((BM + 2 * BN_PAD) * 4 + 1023) / 1024 * 1024;
+    static constexpr int LDS_ALLOC = LDS_BYTES >= LORA_PLANES_BYTES + SCALE_BYTES ? LDS_BYTES : LORA_PLANES_BYTES + SCALE_BYTES;
+    static constexpr int EPI_LIMIT = LDS_ALLOC - SCALE_BYTES;
+    static_assert(BM % 64 == 0, "row scales are staged 64 at a time");
 };
 
 // Tile order.  Workgroups are dealt to the eight XCDs round-robin by the hardware and every XCD has its own L2, so
@@ -58,11 +64,7 @@ __device__ __forceinline__ void gemm_mainloop_dma(const int8_t* __restrict__ gA,
     constexpr int TM = C::TM, TN = C::TN, NLOAD = C::NLOAD, STAGES = C::STAGES_;
 
     auto issue = [&](int tile, int stage) {
-#ifdef QUAFF_TILED_PROBE
-        const int64_t k0 = (int64_t)tile * 1024;
-#else
         const int64_t k0 = (int64_t)tile * C::BK;
-#endif
 #pragma unroll
         for (int j = 0; j < NLOAD; ++j) {
             // group q of the stage: A rows first, then B rows.  A wavefront whose last slot falls past the end repeats
@@ -94,11 +96,6 @@ __device__ __forceinline__ void gemm_mainloop_dma(const int8_t* __restrict__ gA,
     // issue order inside a half step: one LDS read (and at most one direct load), then a share of the MFMAs
     constexpr int MFMA_PER_READ = (TM * TN) / (TM + TN) > 0 ? (TM * TN) / (TM + TN) : 1;
 
-#ifdef QUAFF_GEMM_TIMING
-    long long quaff_timing[2] = {0, 0};
-    long long tstart_ = __builtin_amdgcn_s_memtime();
-    long long wstart_ = wall_clock64();
-#endif
     // prologue: fill the ring (tiles beyond the last are clamped to it: harmless rewrites of a free stage)
 #pragma unroll
     for (int s = 0; s < STAGES; ++s) issue(s < KT ? s : KT - 1, s);
@@ -107,16 +104,11 @@ __device__ __forceinline__ void gemm_mainloop_dma(const int8_t* __restrict__ gA,
 
     i32x4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
     read_frags(0, 0, fa0, fb0);
-#ifdef QUAFF_ABL_NOLDS
-    read_frags(0, 1, fa1, fb1);
-#endif
     int stage = 0;
     for (int kt = 0; kt < KT; ++kt) {
         const int next = (stage + 1 == STAGES) ? 0 : stage + 1;
         // first half: fragments of the second 32 bytes arrive while the first 32 are multiplied
-#ifndef QUAFF_ABL_NOLDS
         read_frags(stage, 1, fa1, fb1);
-#endif
         mfmas(fa0, fb0);
 #pragma unroll
         for (int u = 0; u < TM + TN; ++u) {
@@ -124,34 +116,15 @@ __device__ __forceinline__ void gemm_mainloop_dma(const int8_t* __restrict__ gA,
             __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_READ, 0);
         }
         // every wavefront has now read all of `stage`; tile kt+1 must have landed for everybody
-#ifdef QUAFF_GEMM_TIMING
-        long long t0_ = __builtin_amdgcn_s_memtime();
-#endif
-#ifndef QUAFF_ABL_NOSYNC
         QUAFF_WAIT_VMCNT((STAGES - 2) * NLOAD);
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#endif
-#ifdef QUAFF_GEMM_TIMING
-        long long t1_ = __builtin_amdgcn_s_memtime();
-#endif
-#ifndef QUAFF_ABL_NOSYNC
         __builtin_amdgcn_s_barrier();
-#endif
         asm volatile("" ::: "memory");
-#ifdef QUAFF_GEMM_TIMING
-        long long t2_ = __builtin_amdgcn_s_memtime();
-        quaff_timing[0] += t1_ - t0_;
-        quaff_timing[1] += t2_ - t1_;
-#endif
-#ifndef QUAFF_ABL_NODMA
         {
             int t = kt + STAGES;
             issue(t < KT ? t : KT - 1, stage);
         }
-#endif
-#ifndef QUAFF_ABL_NOLDS
         read_frags(next, 0, fa0, fb0);
-#endif
         mfmas(fa1, fb1);
 #pragma unroll
         for (int u = 0; u < TM + TN; ++u) {
@@ -162,13 +135,6 @@ __device__ __forceinline__ void gemm_mainloop_dma(const int8_t* __restrict__ gA,
         stage = next;
     }
     QUAFF_WAIT_VMCNT(0);
-#ifdef QUAFF_GEMM_TIMING
-    if ((threadIdx.x & 63) == 0 && blockIdx.x < 64) {
-        long long tend_ = __builtin_amdgcn_s_memtime();
-        long long* o = quaff_timing_out + (blockIdx.x * 8 + (threadIdx.x >> 6)) * 4;
-        o[0] = quaff_timing[0]; o[1] = wall_clock64() - wstart_; o[2] = tend_ - tstart_; o[3] = KT;
-    }
-#endif
 }
 
 // Variant of the main loop that consumes TWO 64-byte contraction steps per barrier (ring of four stages): half as
@@ -255,7 +221,182 @@ __device__ __forceinline__ void gemm_mainloop_dma2(const int8_t* __restrict__ gA
     QUAFF_WAIT_VMCNT(0);
 }
 
-template <int BM, int BN, int WGM, int WGN, int STAGES, bool DUMP, int MINB = 1, int PAIR = 0>
+// Epilogue of the fast kernel.  The operands of the short second product (A2, B2) and of the low-rank term (T, L)
+// are first copied into the now idle LDS ring with direct loads - one memory round trip for the whole workgroup
+// instead of one per 32x32 block - in the same 64-byte-row, XOR-swizzled layout as the main loop's stages, then:
+//   phase A  acc2 = A2 B2^T per block (int32, exact); the block becomes  row_scale * (acc * cs + acc2 * cs2)  in fp32
+//   phase B  the low-rank products accumulate onto the fp32 block, 32 columns of r per staging round
+//   phase C  stores (all loads precede all stores: they share one in-order counter)
+// The caller guarantees (K2 / 64) * K2_PLANES_BYTES <= EPI_LIMIT.
+template <class C>
+__device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (&acc)[C::TM][C::TN],
+                                                     lds_i8* __restrict__ dma, const lds_i8* __restrict__ rd,
+                                                     int64_t m0, int64_t n0, int wm, int wn, int wave, int lane) {
+    constexpr int TM = C::TM, TN = C::TN, BM = C::BM_, BN = C::BN_;
+    constexpr int PLANE_A = BM * 64;
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int nk = g.K2 / 64, nl = (g.r + 31) / 32;
+    const int k2_bytes = nk * C::K2_PLANES_BYTES;
+    const bool overlap = k2_bytes + C::LORA_PLANES_BYTES <= C::EPI_LIMIT;   // both operand sets fit side by side
+    const int lora_off = overlap ? k2_bytes : 0;
+    const int64_t row0 = m0 + wm * C::WM, col0 = n0 + wn * C::WN;
+
+    // loader: as in the main loop, one direct load fills 16 rows x 64 bytes; lane -> (row, swizzled 16-byte chunk)
+    const int ld_r = lane >> 2, ld_chunk = (lane & 3) ^ ((lane >> 4) & 3);
+    auto fill = [&](int lds_off, int nrows, auto src_of) {
+        for (int q = wave; q < nrows / 16; q += C::NW)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src_of(q * 16 + ld_r),
+                                             (__attribute__((address_space(3))) void*)(dma + lds_off + q * 1024), 16, 0, 0);
+    };
+    auto a_row = [&](int local) { int64_t r = m0 + local; return r < g.M ? r : g.M - 1; };   // clamped: never stored
+    auto b_row = [&](int local) { int64_t r = n0 + local; return r < g.N ? r : g.N - 1; };
+    auto issue_k2 = [&]() {
+        for (int kk = 0; kk < nk; ++kk) {
+            const int off = kk * C::K2_PLANES_BYTES, kb = kk * 64 + ld_chunk * 16;
+            fill(off, BM, [&](int local) { return g.A2 + a_row(local) * g.K2 + kb; });
+            fill(off + PLANE_A, BN, [&](int local) { return g.B2 + b_row(local) * g.K2 + kb; });
+        }
+    };
+    auto issue_lora = [&](int lc) {
+        // columns [32 lc, 32 lc + 32) of r; a chunk past r repeats chunk 0 (it is never multiplied)
+        const int pc = lc * 32 + (lc * 32 + ld_chunk * 8 < g.r ? ld_chunk * 8 : 0);
+#pragma unroll
+        for (int part = 0; part < kLoraParts; ++part) {
+            const int64_t po = (int64_t)part * g.M * g.r + pc;
+            fill(lora_off + (2 * part) * PLANE_A, BM, [&](int local) { return g.T_hi + po + a_row(local) * g.r; });
+            fill(lora_off + (2 * part + 1) * PLANE_A, BM, [&](int local) { return g.T_lo + po + a_row(local) * g.r; });
+        }
+        fill(lora_off + 2 * kLoraParts * PLANE_A, BN, [&](int local) { return g.L + b_row(local) * g.r + pc; });
+    };
+    auto landed = [&]() {
+        QUAFF_WAIT_VMCNT(0);
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+    // fragment of the 32-row block that starts at plane row `base` (a multiple of 32): this lane's row, chunk c
+    auto frag = [&](int plane_off, int base, int c) {
+        return *(const lds_i32x4*)(rd + plane_off + (base + l32) * 64 + ((c ^ ((l32 >> 2) & 3)) * 16));
+    };
+
+    // every wavefront has finished its main-loop reads and its own direct loads before the ring is reused
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    issue_k2();
+    if (overlap && nl > 0) issue_lora(0);
+
+    // scales: 64 floats per direct load into the planes rs [BM], cs [BN_PAD], cs2 [BN_PAD]
+    {
+        constexpr int NA = BM / 64, NB = C::BN_PAD / 64;
+        for (int q = wave; q < NA + 2 * NB; q += C::NW) {
+            const float* src;
+            if (q < NA) {
+                src = g.row_scale + a_row(q * 64 + lane);
+            } else {
+                const int qb = q - NA < NB ? q - NA : q - NA - NB;
+                const float* base = q - NA < NB ? g.col_scale : g.col_scale2;
+                if (base == nullptr) continue;
+                src = base + b_row(qb * 64 + lane);
+            }
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                             (__attribute__((address_space(3))) void*)(dma + C::EPI_LIMIT + q * 256), 4, 0, 0);
+        }
+    }
+    const lds_i8* rs_plane = rd + C::EPI_LIMIT;
+    const lds_i8* cs_plane = rs_plane + BM * 4;
+    const lds_i8* cs2_plane = cs_plane + C::BN_PAD * 4;
+    const bool has_cs = g.col_scale != nullptr, has_cs2 = nk > 0;
+    landed();
+
+    // ---- phase A
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        if (row0 + i * 32 >= g.M) continue;
+        f32x4 rs[4];   // this lane's 16 output rows of the block are 4 runs of 4 consecutive rows
+#pragma unroll
+        for (int vg = 0; vg < 4; ++vg)
+            rs[vg] = *(const lds_f32x4*)(rs_plane + (wm * C::WM + i * 32 + vg * 8 + lhi * 4) * 4);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            if (col0 + j * 32 >= g.N) continue;
+            const int lcol = wn * C::WN + j * 32 + l32;
+            const float cs = has_cs ? *(const lds_f32*)(cs_plane + lcol * 4) : 1.0f;
+            const float cs2 = has_cs2 ? *(const lds_f32*)(cs2_plane + lcol * 4) : 0.0f;
+            i32x16 acc2;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc2[v] = 0;
+            for (int kk = 0; kk < nk; ++kk) {
+                const int off = kk * C::K2_PLANES_BYTES;
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+                    acc2 = __builtin_amdgcn_mfma_i32_32x32x32_i8(frag(off, wm * C::WM + i * 32, ks * 2 + lhi),
+                                                                 frag(off + PLANE_A, wn * C::WN + j * 32, ks * 2 + lhi),
+                                                                 acc2, 0, 0, 0);
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float inner = __builtin_fmaf((float)acc[i][j][v], cs, (float)acc2[v] * cs2);
+                acc[i][j][v] = __float_as_int(rs[v >> 2][v & 3] * inner);
+            }
+        }
+    }
+
+    // ---- phase B
+    for (int lc = 0; lc < nl; ++lc) {
+        if (!(overlap && lc == 0)) {
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();          // everybody has read what the next loads overwrite
+            asm volatile("" ::: "memory");
+            issue_lora(lc);
+            landed();
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            if (row0 + i * 32 >= g.M) continue;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                if (col0 + j * 32 >= g.N) continue;
+                f32x16 c = __builtin_bit_cast(f32x16, acc[i][j]);
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {           // 16 columns of r per MFMA
+                    if (lc * 32 + h * 16 >= g.r) continue;
+                    const bf16x8 lb = __builtin_bit_cast(
+                        bf16x8, frag(lora_off + 2 * kLoraParts * PLANE_A, wn * C::WN + j * 32, h * 2 + lhi));
+#pragma unroll
+                    for (int pl = 0; pl < 2 * kLoraParts; ++pl)
+                        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, frag(lora_off + pl * PLANE_A, wm * C::WM + i * 32, h * 2 + lhi)),
+                            lb, c, 0, 0, 0);
+                }
+                acc[i][j] = __builtin_bit_cast(i32x16, c);
+            }
+        }
+    }
+
+    // ---- phase C
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int64_t ib = row0 + i * 32;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int64_t jb = col0 + j * 32, col = jb + l32;
+            if (ib >= g.M || jb >= g.N) continue;
+            float* out = g.C + (ib + lhi * 4) * g.ldc + col;
+            if (ib + 32 <= g.M && jb + 32 <= g.N) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) out[((v >> 2) * 8 + (v & 3)) * g.ldc] = __int_as_float(acc[i][j][v]);
+            } else {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    int64_t row = ib + (v >> 2) * 8 + lhi * 4 + (v & 3);
+                    if (row < g.M && col < g.N) out[((v >> 2) * 8 + (v & 3)) * g.ldc] = __int_as_float(acc[i][j][v]);
+                }
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int WGM, int WGN, int STAGES, bool DUMP, int MINB = 1, int PAIR = 0, bool STAGED = false>
 __global__ void __launch_bounds__(64 * WGM * WGN, MINB)
 gemm_i8_dma_kernel(const GemmArgs g, const TileMap tmap) {
     using C = DmaCfg<BM, BN, WGM, WGN, STAGES>;
@@ -284,11 +425,7 @@ gemm_i8_dma_kernel(const GemmArgs g, const TileMap tmap) {
             int64_t row = (isA ? m0 : n0) + local;
             int64_t lim = (isA ? g.M : g.N) - 1;
             row = row < lim ? row : lim;                        // clamp: rows past the edge are never stored
-#ifdef QUAFF_TILED_PROBE
-            voff[j] = (uint32_t)((((isA ? m0 : n0) / 16 + (isA ? q : q - BM / 16)) % ((isA ? g.M : g.N) / 16)) * (g.K * 16) + lane * 16);
-#else
             voff[j] = (uint32_t)(row * (isA ? g.lda : g.ldb) + chunk * 16);
-#endif
         }
     }
     const int frag = l32 * 64 + ((lhi ^ ((l32 >> 2) & 3)) * 16);
@@ -307,16 +444,10 @@ gemm_i8_dma_kernel(const GemmArgs g, const TileMap tmap) {
     else
         gemm_mainloop_dma<C>(g.A, g.B, voff, (int)(g.K / C::BK), lds, lds, wave, a_frag_off, b_frag_off, acc);
 
-#ifdef QUAFF_GEMM_TIMING
-    long long te0_ = __builtin_amdgcn_s_memtime();
-#endif
-    gemm_epilogue<C::TM, C::TN, DUMP>(g, acc, m0 + wm * C::WM, n0 + wn * C::WN, l32, lhi);
-#ifdef QUAFF_GEMM_TIMING
-    if ((threadIdx.x & 63) == 0 && blockIdx.x < 64) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        quaff_timing_out[(blockIdx.x * 8 + (threadIdx.x >> 6)) * 4 + 3] = __builtin_amdgcn_s_memtime() - te0_;
-    }
-#endif
+    if constexpr (STAGED && !DUMP)
+        gemm_epilogue_staged<C>(g, acc, lds, lds, m0, n0, wm, wn, wave, lane);
+    else
+        gemm_epilogue<C::TM, C::TN, DUMP>(g, acc, m0 + wm * C::WM, n0 + wn * C::WN, l32, lhi);
 }
 
 // host side: choose the XCD region grid for a tile grid
