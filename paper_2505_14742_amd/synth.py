@@ -285,6 +285,13 @@ EDGE_CASES = [
              max_in_outlier_rows=[1, 2]),
     EdgeCase("ragged_rows", 2048 + 3, 512, 528, [1, 2, 3, 500], 16),
     EdgeCase("single_row", 1, 256, 256, [9], 16),
+    # shapes that reach every output-tile shape of the GEMM with short contractions (cheap on the CPU), crossed
+    # with outlier counts of one to four 64-wide slices and LoRA ranks of one or two 32-column slices
+    EdgeCase("wide_out_n65_r64", 2048, 256, 9216, list(range(1, 256, 3))[:65], 64),
+    EdgeCase("wide_out_odd_steps_r48", 2048, 192, 9216, [0, 50, 100, 150, 191], 48),
+    EdgeCase("very_wide_out_n70_r32", 1024, 256, 16384, list(range(2, 256, 3))[:70], 32),
+    EdgeCase("mid_out_n200_r16", 2048, 256, 4096, list(range(0, 250))[:200], 16),
+    EdgeCase("mid_out_n130_r64", 2048, 256, 4096, list(range(0, 256, 1))[60:190], 64),
 ]
 
 
