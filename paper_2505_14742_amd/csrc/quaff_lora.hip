@@ -18,7 +18,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kLoraWaves = 16;
-constexpr int kLoraUnroll = 6;   // contraction steps whose loads are issued together (latency hiding)
+constexpr int kLoraUnroll = 6;   // contraction steps whose loads are issued together (latency hiding); even
 
 __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
     uint32_t u = __float_as_uint(f);
@@ -59,9 +59,10 @@ lora_down_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx, 
 
     // each wavefront owns one contiguous slice of the contraction range (kw columns), walked in 32-column steps
     // this workgroup's part of the contraction range, then this wavefront's slice of it
-    const int cp = ((c + kLoraParts * 32 - 1) / (kLoraParts * 32)) * 32;
+    // (multiples of 64 columns = 128 bytes, so that a pair of steps reads whole cache lines, see below)
+    const int cp = ((c + kLoraParts * 64 - 1) / (kLoraParts * 64)) * 64;
     const int cbeg = blockIdx.y * cp, cend = cbeg + cp < c ? cbeg + cp : c;
-    const int kw = ((cend - cbeg + kLoraWaves * 32 - 1) / (kLoraWaves * 32)) * 32;
+    const int kw = ((cend - cbeg + kLoraWaves * 64 - 1) / (kLoraWaves * 64)) * 64;
     const int kbeg = cbeg + wave * kw, kend = kbeg + kw < cend ? kbeg + kw : cend;
     T_hi += (int64_t)blockIdx.y * t * r;
     T_lo += (int64_t)blockIdx.y * t * r;
@@ -70,8 +71,12 @@ lora_down_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx, 
         // all global loads of the batch first
 #pragma unroll
         for (int u = 0; u < kLoraUnroll; ++u) {
-            const int k0 = kk0 + u * 32;
-            const int k = k0 + g * 8;          // this lane's eight contraction indices
+            // Two consecutive steps share 64 columns: lane group g takes columns 16 g .. 16 g + 7 in the even step
+            // and 16 g + 8 .. 16 g + 15 in the odd one (any assignment of contraction indices to MFMA slots is
+            // valid as long as both operands use it), so the four groups of a row read one whole 128-byte line
+            // per step pair instead of two half lines.
+            const int k0 = kk0 + (u >> 1) * 64 + (u & 1) * 8;
+            const int k = k0 + g * 16;         // this lane's eight contraction indices
             // loads are unconditional (address clamped into the row) so that the whole batch is in flight together;
             // a step past the end contributes zero because its x fragment is cleared
             const int kc = k < kend ? k : c - 8;
@@ -88,7 +93,8 @@ lora_down_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx, 
                 for (int b = 0; b < R16; ++b) {   // VEC = 64 * R16: one vector per lane per b
                     int v = b * 64 + lane;
                     int kk = v / (r / 8), p0 = (v % (r / 8)) * 8;
-                    const int kr = k0 + kk < c ? k0 + kk : c - 1;
+                    const int km = k0 + (kk >> 3) * 16 + (kk & 7);   // slot kk of the step holds this column
+                    const int kr = km < c ? km : c - 1;
                     lb[u][b] = *reinterpret_cast<const u32x4*>(L + (int64_t)kr * r + p0);
                 }
                 (void)VEC;

@@ -17,6 +17,7 @@ namespace quaff {
 constexpr int kRowsPerSlab = 16;
 constexpr int kMaxSlabs = 128;
 constexpr int kWhatThreads = 128;   // output channels per workgroup of momentum_what_kernel
+constexpr int kPartBatch = 32;     // partial maxima loaded per thread before the first is used
 
 int scale_update_blocks(int64_t t) {
     int64_t b = (t + kRowsPerSlab - 1) / kRowsPerSlab;
@@ -82,15 +83,15 @@ momentum_what_kernel(const uint32_t* __restrict__ part, int nslab, int n, int n_
     for (int k = threadIdx.x; k < n; k += kWhatThreads) smax[k] = 0u;
     __syncthreads();
     const int total = nslab * n;
-    for (int e0 = threadIdx.x; e0 < total; e0 += 8 * kWhatThreads) {   // eight independent loads in flight per thread
-        uint32_t v[8];
+    for (int e0 = threadIdx.x; e0 < total; e0 += kPartBatch * kWhatThreads) {   // one round trip for up to 4096 partials
+        uint32_t v[kPartBatch];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < kPartBatch; ++u) {
             int e = e0 + u * kWhatThreads;
             v[u] = part[e < total ? e : total - 1];
         }
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < kPartBatch; ++u) {
             int e = e0 + u * kWhatThreads;
             if (e < total) atomicMax(&smax[e % n], v[u]);
         }
@@ -155,7 +156,10 @@ hipError_t launch_scale_update(const uint16_t* X, int64_t t, int64_t c_in, int64
                                float* colscale, int8_t* what_int, float* delta_what, float* cmax_out, float* ws,
                                hipStream_t stream) {
     (void)c_in;
+    // as many slabs as the rows allow, but no more partial maxima than momentum_what_kernel reduces in one batch
     int nslab = scale_update_blocks(t);
+    const int one_batch = kPartBatch * kWhatThreads / n;
+    if (nslab > one_batch) nslab = one_batch > 16 ? one_batch : 16;
     int n_pad = (n + kPadK - 1) / kPadK * kPadK;
     uint32_t* part = reinterpret_cast<uint32_t*>(ws);   // [nslab x n]
     float* s_prev = ws + (int64_t)nslab * n;            // [n]
