@@ -119,6 +119,15 @@ def main():
     total_ops = sum(L["fwd_ops"] + L["bwd_ops"] for L in layers)
     tops = total_ops / (ms_per_step * 1e-3) / 1e12
 
+    # "warm" variant for comparison: the same batch every step (inputs and outputs may stay in the Infinity Cache);
+    # the headline figures above are the rotated ("cold") ones
+    e0.record()
+    for i in range(args.steps):
+        step(0)
+    e1.record()
+    torch.cuda.synchronize()
+    warm_ms_per_step = e0.elapsed_time(e1) / args.steps
+
     # ---- per-kernel durations with HIP events on the launch stream (separate pass: the events perturb the step)
     q.profile_enable(True)
     prof_steps = min(args.steps, 20)
@@ -180,6 +189,35 @@ def main():
                       "us_per_step": round(v[0] / prof_steps * 1e3, 2)} for name, v in kinds.items()}
     kernels["quant_rows"]["achieved_GBs"] = round(quant_bytes / (quant_ms * 1e-3) / 1e9, 1)
     kernels["quant_rows"]["frac_hbm_peak"] = round(quant_bytes / (quant_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+    # LoRA down-projection: reads the activation (or dY) and the factor once, writes the hi/lo partial sums
+    lora_bytes = 0.0
+    for L in layers:
+        p, r = L["p"], L["r"]
+        if r:
+            lora_bytes += 2.0 * p.t * p.c_in + 2.0 * p.c_in * r + 8.0 * p.t * r + 4.0 * p.c_out * r
+            if p.backward:
+                lora_bytes += 2.0 * p.t * p.c_out + 2.0 * p.c_out * r + 8.0 * p.t * r
+    if "lora_down" in kernels and lora_bytes:
+        lora_ms = kinds["lora_down"][0] / prof_steps
+        kernels["lora_down"]["achieved_GBs"] = round(lora_bytes / (lora_ms * 1e-3) / 1e9, 1)
+        kernels["lora_down"]["frac_hbm_peak"] = round(lora_bytes / (lora_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+    # column abs-max: useful bytes are the 2-byte outlier entries; what the memory system must fetch is one
+    # 64-byte segment per (row, distinct segment touched by O) - counted here from the outlier positions
+    if "colmax_outlier" in kernels:
+        useful = fetched = 0.0
+        for L in layers:
+            if L["n"]:
+                seg = len(set(int(o) // 32 for o in L["O"].cpu().tolist()))
+                useful += 2.0 * L["p"].t * L["n"]
+                fetched += 64.0 * L["p"].t * seg
+        col_ms = kinds["colmax_outlier"][0] / prof_steps
+        kernels["colmax_outlier"]["useful_GBs"] = round(useful / (col_ms * 1e-3) / 1e9, 1)
+        kernels["colmax_outlier"]["fetched_GBs"] = round(fetched / (col_ms * 1e-3) / 1e9, 1)
+        kernels["colmax_outlier"]["frac_hbm_peak_fetched"] = round(fetched / (col_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+    for name, v in kinds.items():
+        ds = sorted(ms for nm, ms in launches if nm == name)
+        kernels[name]["min_us"] = round(ds[0] * 1e3, 2)
+        kernels[name]["median_us"] = round(ds[len(ds) // 2] * 1e3, 2)
 
     out = {
         "metric": "INT8 quantized-linear TOPS fwd+bwd_dx at Phi-3 shapes; % INT8 MFMA peak",
@@ -200,6 +238,7 @@ def main():
             "scale_update, quant_act, linear_fwd, linear_bwd_dx per projection"},
         "frac_int8_peak_whole_step": round(tops / INT8_PEAK_TOPS, 4),
         "wall_ms_per_step": round(wall_ms / args.steps, 5),
+        "warm_same_batch_ms_per_step": round(warm_ms_per_step, 5),
         "roofline": {"bound": "mfma", "kernel": "gemm_i8 (all launches of the step)", "achieved": round(gemm_tops, 2),
                      "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": round(gemm_tops / INT8_PEAK_TOPS, 4),
                      "traffic": gemm_traffic, "traffic_unit": "bytes per GEMM launch (rocprofv3 FETCH_SIZE + "
@@ -248,7 +287,21 @@ def main():
                     ops += 2.0 * p.t * p.c_out * p.c_in
             secs += time.perf_counter() - t0
             nsteps += 1
-        out["cpu_baseline"] = {"value": round(ops / secs / 1e12, 5), "unit": "TOPS", "cores": orc.max_threads(),
+        # one thread, first projection's forward only (bounded: the whole step would take about ten times longer)
+        orc.set_threads(1)
+        S, (X, dY) = state[-1], batches[0][-1]
+        p = S["p"]
+        t0 = time.perf_counter()
+        _s, _cs, what, dwh, _ = orc.scale_update(X, S["O"], S["W_O"], S["wmax"], p.gamma, S["s"].copy(), S["cs"].copy())
+        Xq, dx, xo = orc.quant_act(X, _cs, S["O"])
+        orc.linear_fwd(Xq, dx, xo, S["Wq"], S["dw"], what, dwh, X, S["A"], S["B"], p.lora_scale)
+        one_secs = time.perf_counter() - t0
+        one_tops = 2.0 * p.t * p.c_out * (p.c_in + S["O"].size) / one_secs / 1e12
+        orc.set_threads(min(orc.max_threads(), 16))
+        out["cpu_baseline"] = {"single_thread": {"value": round(one_tops, 5), "unit": "TOPS", "cores": 1,
+                                                 "seconds": round(one_secs, 2),
+                                                 "sample": "forward of %s (scale update, quantize, forward)" % p.name},
+                               "value": round(ops / secs / 1e12, 5), "unit": "TOPS", "cores": orc.max_threads(),
                                "kind": "oracle", "seconds": round(secs, 2),
                                "sample": "%d whole step(s) of the same workload (every projection, all %d rows: scale "
                                          "update, quantize, forward, dX)" % (nsteps, layers[0]["p"].t)}

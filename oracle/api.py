@@ -167,3 +167,42 @@ def ref_bwd_fp64(dY, W, lora_A=None, lora_B=None, lora_scale=0.0):
     lib().oracle_ref_bwd_fp64(_p(dY), i64(t), i64(N), i64(N), _p(W), i64(K), _p(A), _p(B), i32(r), f32(lora_scale),
                               _p(dX))
     return dX
+
+
+def lora_grads(X, dY, lora_A, lora_B, lora_scale):
+    """Returns (dA [c_in x r], dB [r x c_out]) in fp64."""
+    X = _c(X, np.uint16)
+    dY = _c(dY, np.uint16)
+    A = _c(lora_A, np.uint16)
+    B = _c(lora_B, np.uint16)
+    t, K = X.shape
+    N = dY.shape[1]
+    r = A.shape[1]
+    assert dY.shape[0] == t and A.shape[0] == K and B.shape == (r, N)
+    dA = np.empty((K, r), np.float64)
+    dB = np.empty((r, N), np.float64)
+    lib().oracle_lora_grads(_p(X), _p(dY), i64(t), i64(K), i64(N), i64(K), i64(N), _p(A), _p(B), i32(r),
+                            f32(lora_scale), _p(dA), _p(dB))
+    return dA, dB
+
+
+def bwd_dx_outlier_cols(dY, O, W_O, Wq=None, delta_w=None, what_int=None, delta_what=None, colscale=None,
+                        lora_A=None, lora_B=None, lora_scale=0.0):
+    """Returns (exact [t x n], ste [t x n] or None) in fp64; ste needs Wq, delta_w, what_int, delta_what, colscale."""
+    dY = _c(dY, np.uint16)
+    O = _c(O, np.int32)
+    W_O = _c(W_O, np.float32)
+    t, N = dY.shape
+    n = O.size
+    r = 0 if lora_A is None else lora_A.shape[1]
+    A = _c(lora_A, np.uint16) if r > 0 else None
+    B = _c(lora_B, np.uint16) if r > 0 else None
+    exact = np.empty((t, n), np.float64)
+    want_ste = Wq is not None
+    ste = np.empty((t, n), np.float64) if want_ste else None
+    lib().oracle_bwd_dx_outlier_cols(
+        _p(dY), i64(t), i64(N), i64(N), _p(O), i32(n), _p(W_O), _p(_c(Wq, np.int8)) if want_ste else None,
+        _p(_c(delta_w, np.float32)) if want_ste else None, _p(_c(what_int, np.int8)) if want_ste else None,
+        _p(_c(delta_what, np.float32)) if want_ste else None, _p(_c(colscale, np.float32)) if want_ste else None,
+        _p(A), _p(B), i32(r), f32(lora_scale), _p(exact), _p(ste))
+    return exact, ste

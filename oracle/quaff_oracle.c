@@ -351,6 +351,99 @@ void oracle_ref_bwd_fp64(const uint16_t* dY, int64_t t, int64_t c_out, int64_t l
     }
 }
 
+/* ------------------------------------------------------------------------
+ * LoRA weight gradients of the adapter branch Y_l = lora_scale (X A) B (App.
+ * "Model and experimental settings": LoRA on every linear layer; the frozen
+ * quantized weight gets no gradient, Sec. 2.1).  Plain calculus on the bf16
+ * input values, fp64 throughout:
+ *   dA[k,p] = lora_scale * sum_i X[i,k]  * (sum_j dY[i,j] B[p,j])
+ *   dB[p,j] = lora_scale * sum_i (sum_k X[i,k] A[k,p]) * dY[i,j]
+ * Reading (the paper is silent): the adapter's backward uses the unquantized
+ * X and dY, like its forward; no dropout.
+ * Out: dA [c_in x r], dB [r x c_out] (fp64; callers round to fp32).
+ * ---------------------------------------------------------------------- */
+void oracle_lora_grads(const uint16_t* X, const uint16_t* dY, int64_t t, int64_t c_in, int64_t c_out, int64_t ldx,
+                       int64_t lddy, const uint16_t* lora_A, const uint16_t* lora_B, int32_t r, float lora_scale,
+                       double* dA, double* dB) {
+    double* T1 = (double*)malloc(sizeof(double) * (size_t)(t * r + 1)); /* dY B^T */
+    double* T2 = (double*)malloc(sizeof(double) * (size_t)(t * r + 1)); /* X A    */
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < t; ++i)
+        for (int32_t p = 0; p < r; ++p) {
+            double s1 = 0.0, s2 = 0.0;
+            for (int64_t j = 0; j < c_out; ++j)
+                s1 += (double)bf16_to_f32(dY[i * lddy + j]) * (double)bf16_to_f32(lora_B[(int64_t)p * c_out + j]);
+            for (int64_t k = 0; k < c_in; ++k)
+                s2 += (double)bf16_to_f32(X[i * ldx + k]) * (double)bf16_to_f32(lora_A[k * r + p]);
+            T1[i * r + p] = s1;
+            T2[i * r + p] = s2;
+        }
+#pragma omp parallel for schedule(static)
+    for (int64_t k = 0; k < c_in; ++k)
+        for (int32_t p = 0; p < r; ++p) {
+            double s = 0.0;
+            for (int64_t i = 0; i < t; ++i) s += (double)bf16_to_f32(X[i * ldx + k]) * T1[i * r + p];
+            dA[k * r + p] = (double)lora_scale * s;
+        }
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < c_out; ++j)
+        for (int32_t p = 0; p < r; ++p) {
+            double s = 0.0;
+            for (int64_t i = 0; i < t; ++i) s += T2[i * r + p] * (double)bf16_to_f32(dY[i * lddy + j]);
+            dB[(int64_t)p * c_out + j] = (double)lora_scale * s;
+        }
+    free(T1);
+    free(T2);
+}
+
+/* ------------------------------------------------------------------------
+ * Input gradient on the outlier channels, three candidate forms (the paper
+ * does not describe its backward pass; Sec. 3.3 retains W_O in full precision).
+ * For k in O, with T1 = dY B^T and the LoRA term l[i,k] = lora_scale sum_p T1[i,p] A[O_k,p]:
+ *   exact[i,k] = sum_j dY[i,j] W_O[k,j] + l[i,k]
+ *       (true gradient of X W on these columns: s cancels, Eq. 3)
+ *   ste[i,k]   = rinv_k * sum_j dY[i,j] (Wq[O_k,j] delta_w[j] + what_int[k,j] delta_what[j]) + l[i,k]
+ *       (gradient of Eq. 9 as evaluated, quantizers treated as identity; rinv_k = colscale[O_k])
+ * The third form, the s-free quantized product, is oracle_linear_bwd_dx's output at columns O.
+ * Out: exact, ste [t x n] fp64.  Either may be NULL.
+ * ---------------------------------------------------------------------- */
+void oracle_bwd_dx_outlier_cols(const uint16_t* dY, int64_t t, int64_t c_out, int64_t lddy, const int32_t* O, int32_t n,
+                                const float* W_O, const int8_t* Wq, const float* delta_w, const int8_t* what_int,
+                                const float* delta_what, const float* colscale, const uint16_t* lora_A,
+                                const uint16_t* lora_B, int32_t r, float lora_scale, double* exact, double* ste) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < t; ++i) {
+        double* T1 = (double*)malloc(sizeof(double) * (size_t)(r > 0 ? r : 1));
+        for (int32_t p = 0; p < r; ++p) {
+            double s = 0.0;
+            for (int64_t j = 0; j < c_out; ++j)
+                s += (double)bf16_to_f32(dY[i * lddy + j]) * (double)bf16_to_f32(lora_B[(int64_t)p * c_out + j]);
+            T1[p] = s;
+        }
+        for (int32_t k = 0; k < n; ++k) {
+            double l = 0.0;
+            for (int32_t p = 0; p < r; ++p) l += T1[p] * (double)bf16_to_f32(lora_A[(int64_t)O[k] * r + p]);
+            l *= (double)lora_scale;
+            if (exact) {
+                double s = 0.0;
+                for (int64_t j = 0; j < c_out; ++j)
+                    s += (double)bf16_to_f32(dY[i * lddy + j]) * (double)W_O[(int64_t)k * c_out + j];
+                exact[i * n + k] = s + l;
+            }
+            if (ste) {
+                double s = 0.0;
+                for (int64_t j = 0; j < c_out; ++j) {
+                    double w = (double)Wq[(int64_t)O[k] * c_out + j] * (double)delta_w[j] +
+                               (double)what_int[(int64_t)k * c_out + j] * (double)delta_what[j];
+                    s += (double)bf16_to_f32(dY[i * lddy + j]) * w;
+                }
+                ste[i * n + k] = (double)colscale[O[k]] * s + l;
+            }
+        }
+        free(T1);
+    }
+}
+
 /* thread control for the row-parallel loops (rows are independent in every step but the column max) */
 #ifdef _OPENMP
 #include <omp.h>

@@ -413,6 +413,104 @@ def test_split_run_equals_straight_run():
     assert np.all(s_a >= 1.0)
 
 
+# ------------------------------------------------------------------ P13: LoRA weight gradients
+def test_lora_weight_gradients_directional_derivatives_and_special_cases():
+    Xb, W, O, A, B, dY = small_problem(101, t=29, K=72, N=40, r=16)
+    X64, G64, A64, B64 = (f32(v).astype(np.float64) for v in (Xb, dY, A, B))
+    scale = 0.75
+    dA, dB = orc.lora_grads(Xb, dY, A, B, scale)
+    assert dA.shape == A.shape and dB.shape == B.shape
+    # the branch is linear in A and in B, so <dA, E> is exactly the change of <dY, Y_l> when A moves by E
+    rng = np.random.default_rng(5)
+    for _ in range(3):
+        EA, EB = rng.standard_normal(A.shape), rng.standard_normal(B.shape)
+        dL_A = np.sum(G64 * (scale * (X64 @ EA) @ B64))
+        dL_B = np.sum(G64 * (scale * (X64 @ A64) @ EB))
+        assert abs(np.sum(dA * EA) - dL_A) <= 1e-11 * max(abs(dL_A), np.linalg.norm(dA) * np.linalg.norm(EA) * 1e-3)
+        assert abs(np.sum(dB * EB) - dL_B) <= 1e-11 * max(abs(dL_B), np.linalg.norm(dB) * np.linalg.norm(EB) * 1e-3)
+    # a single-entry direction isolates one element: catches transposed or mis-indexed outputs
+    for (k, p_) in ((0, 0), (71, 15), (13, 7)):
+        E = np.zeros(A.shape)
+        E[k, p_] = 1.0
+        assert abs(dA[k, p_] - np.sum(G64 * (scale * (X64 @ E) @ B64))) <= 1e-11 * np.abs(dA).max()
+    for (p_, j) in ((0, 0), (15, 39), (3, 21)):
+        E = np.zeros(B.shape)
+        E[p_, j] = 1.0
+        assert abs(dB[p_, j] - np.sum(G64 * (scale * (X64 @ A64) @ E))) <= 1e-11 * np.abs(dB).max()
+    # special cases and linearity in the scale
+    dA0, dB0 = orc.lora_grads(Xb, dY, A, np.zeros_like(B), scale)
+    assert not dA0.any() and np.array_equal(dB0, dB)
+    dA1, dB1 = orc.lora_grads(Xb, dY, np.zeros_like(A), B, scale)
+    assert not dB1.any() and np.array_equal(dA1, dA)
+    dA2, dB2 = orc.lora_grads(Xb, dY, A, B, 2 * scale)
+    assert rel(dA2, 2 * dA) < 1e-15 and rel(dB2, 2 * dB) < 1e-15
+    assert np.abs(dA).max() > 0 and np.abs(dB).max() > 0
+
+
+def test_lora_weight_gradients_tiny_integers_and_forward_differences():
+    # small integers are exact in bf16 and in every sum, so equality is exact
+    t, K, N, r = 3, 4, 3, 2
+    X = np.array([[1, -2, 0, 3], [2, 1, -1, 0], [0, 3, 1, -2]], np.float32)
+    G = np.array([[1, 0, -1], [2, -1, 0], [-1, 1, 2]], np.float32)
+    A = np.array([[1, 0], [-1, 2], [2, 1], [0, -1]], np.float32)
+    B = np.array([[1, -1, 2], [0, 2, -1]], np.float32)
+    dA, dB = orc.lora_grads(bf(X).reshape(t, K), bf(G).reshape(t, N), bf(A).reshape(K, r), bf(B).reshape(r, N), 1.0)
+    wantA = np.zeros((K, r))
+    wantB = np.zeros((r, N))
+    for i in range(t):
+        for p_ in range(r):
+            t1 = sum(G[i, j] * B[p_, j] for j in range(N))
+            t2 = sum(X[i, k] * A[k, p_] for k in range(K))
+            for k in range(K):
+                wantA[k, p_] += X[i, k] * t1
+            for j in range(N):
+                wantB[p_, j] += t2 * G[i, j]
+    assert np.array_equal(dA, wantA) and np.array_equal(dB, wantB)
+    # forward differences through the oracle's own forward reference: L(A) = <dY, Y*(A)> is linear in A and B
+    W = np.zeros((K, N), np.float32)
+    Xb, Gb = bf(X).reshape(t, K), bf(G).reshape(t, N)
+
+    def loss(A_, B_):
+        return np.sum(G.astype(np.float64) * orc.ref_fwd_fp64(Xb, W, bf(A_).reshape(K, r), bf(B_).reshape(r, N), 1.0))
+
+    EA = np.array([[1, -1], [0, 2], [-2, 0], [1, 1]], np.float32)
+    EB = np.array([[0, 1, -1], [2, 0, 1]], np.float32)
+    assert loss(A + EA, B) - loss(A, B) == np.sum(dA * EA)
+    assert loss(A, B + EB) - loss(A, B) == np.sum(dB * EB)
+
+
+# ------------------------------------------------------------------ P14: input gradient on the outlier channels
+def test_outlier_column_gradient_forms():
+    Xb, W, O, A, B, dY = small_problem(111, t=33, K=96, N=64, n=6, r=16)
+    res = quaff_step(Xb, W, O, np.ones(O.size, np.float32), 0.2, A, B, 1.0)
+    G64 = f32(dY).astype(np.float64)
+    lora = (G64 @ f32(B).astype(np.float64).T) @ f32(A).astype(np.float64)[O].T
+    exact, ste = orc.bwd_dx_outlier_cols(dY, O, res["W_O"], res["Wq"], res["dw"], res["what"], res["dwh"],
+                                         res["colscale"], A, B, 1.0)
+    dXstar = orc.ref_bwd_fp64(dY, W, A, B, 1.0)
+    # exact form = the O columns of the true gradient (itself pinned against numpy above) and of plain numpy
+    assert rel(exact, dXstar[:, O]) < 1e-13
+    assert rel(exact, G64 @ W.astype(np.float64)[O].T + lora) < 1e-13
+    # straight-through form, written out independently
+    Wdeq = res["Wq"].astype(np.float64)[O] * res["dw"].astype(np.float64)[None, :]
+    whdeq = res["what"].astype(np.float64) * res["dwh"].astype(np.float64)[None, :]
+    want = res["colscale"].astype(np.float64)[O][None, :] * (G64 @ (Wdeq + whdeq).T) + lora
+    assert rel(ste, want) < 1e-13
+    # with s = 1 the correction vanishes and the form is dY W_deq^T on these columns
+    ones = np.ones(W.shape[0], np.float32)
+    _, ste1 = orc.bwd_dx_outlier_cols(dY, O, res["W_O"], res["Wq"], res["dw"], np.zeros_like(res["what"]),
+                                      np.zeros_like(res["dwh"]), ones, None, None, 0.0)
+    assert rel(ste1, G64 @ Wdeq.T) < 1e-13
+    # error ranking against the true gradient on these columns: exact (0) < straight-through < s-free quantized
+    dXq, _, _, _ = orc.linear_bwd_dx(dY, res["Wq"], res["dw"], A, B, 1.0)
+    e_ste = rel(ste, dXstar[:, O])
+    e_q = rel(dXq[:, O], dXstar[:, O])
+    assert 0.0 < e_ste < e_q < 0.05
+    # without LoRA arguments the adapter term is absent
+    exact0, _ = orc.bwd_dx_outlier_cols(dY, O, res["W_O"])
+    assert rel(exact0, G64 @ W.astype(np.float64)[O].T) < 1e-13
+
+
 # ------------------------------------------------------------------ planted mistakes are caught by the pins above
 @pytest.mark.parametrize("mistake", ["transposed_w", "dropped_correction", "wrong_sign"])
 def test_pins_are_sensitive(mistake):
