@@ -164,6 +164,24 @@ int quaff_linear_bwd_dx_acc(const uint16_t* dY, int64_t t, int64_t lddy, const v
                             int64_t c_in, int64_t c_out, int8_t* Gq, float* delta_g, int32_t* acc, void* stream);
 
 /*
+ * LoRA weight gradients of the adapter branch lora_scale (X A) B (App. "Model and experimental settings": LoRA on
+ * every linear layer; the frozen quantized weight gets no gradient, Sec. 2.1).  The paper does not describe its
+ * backward pass; the adapter's gradients are taken on the unquantized bf16 X and dY, like its forward, no dropout:
+ *   dA[k, p] = lora_scale * sum_i X[i, k] * (sum_j dY[i, j] B[p, j])
+ *   dB[p, j] = lora_scale * sum_i (sum_k X[i, k] A[k, p]) * dY[i, j]
+ *   in : X [t x c_in] bf16 (ldx), dY [t x c_out] bf16 (lddy), lora_A [c_in x r] bf16, lora_B [r x c_out] bf16,
+ *        lora_rank a multiple of 16 in [16, 64]
+ *   out: dA [c_in x r] fp32, dB [r x c_out] fp32 (dense; overwritten, not accumulated)
+ * `workspace` must hold quaff_lora_bwd_workspace_bytes(t, c_in, c_out, lora_rank) bytes.  fp32 accumulation over
+ * the tokens in a fixed order: results are reproducible from run to run.
+ */
+size_t quaff_lora_bwd_workspace_bytes(int64_t t, int64_t c_in, int64_t c_out, int32_t lora_rank);
+int quaff_lora_bwd_weights(const uint16_t* X, int64_t ldx, const uint16_t* dY, int64_t lddy, int64_t t, int64_t c_in,
+                           int64_t c_out, const uint16_t* lora_A, const uint16_t* lora_B, int32_t lora_rank,
+                           float lora_scale, float* dA, float* dB, void* workspace, size_t workspace_bytes,
+                           void* stream);
+
+/*
  * Optional per-launch kernel timing for benchmarks (not part of the method).  While enabled, every kernel the
  * library launches is bracketed by a pair of HIP events on the caller's stream; this perturbs end-to-end time, so
  * whole-step timing is taken with profiling off.  State is process-wide and guarded by a mutex.

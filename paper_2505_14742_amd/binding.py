@@ -33,6 +33,9 @@ SIGNATURES = {
     "quaff_linear_bwd_dx": (C.c_int, [_vp, _i64, _i64, _vp, _vp, _i64, _i64, _vp, _vp, _i32, _f32, _vp, _i64, _vp,
                                       _sz, _vp]),
     "quaff_linear_bwd_dx_acc": (C.c_int, [_vp, _i64, _i64, _vp, _vp, _i64, _i64, _vp, _vp, _vp, _vp]),
+    "quaff_lora_bwd_workspace_bytes": (_sz, [_i64, _i64, _i64, _i32]),
+    "quaff_lora_bwd_weights": (C.c_int, [_vp, _i64, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _i32, _f32, _vp, _vp, _vp,
+                                         _sz, _vp]),
     "quaff_profile_enable": (C.c_int, [C.c_int]),
     "quaff_profile_collect": (_i64, []),
     "quaff_profile_launch": (C.c_int, [_i64, C.POINTER(C.c_int), C.POINTER(C.c_float)]),
@@ -146,6 +149,19 @@ def linear_bwd_dx(dY, Wq_packed, delta_w, c_in, c_out, lora_A, lora_B, lora_rank
                                      _ptr(workspace),
                                      0 if workspace is None else workspace.numel() * workspace.element_size(),
                                      _stream()))
+
+
+def lora_bwd_workspace_bytes(t, c_in, c_out, lora_rank) -> int:
+    return int(lib().quaff_lora_bwd_workspace_bytes(t, c_in, c_out, lora_rank))
+
+
+def lora_bwd_weights(X, dY, lora_A, lora_B, lora_rank, lora_scale, dA, dB, workspace):
+    t, c_in, c_out = X.shape[0], X.shape[1], dY.shape[1]
+    _check(lib().quaff_lora_bwd_weights(_ptr(X), X.stride(0), _ptr(dY), dY.stride(0), t, c_in, c_out, _ptr(lora_A),
+                                        _ptr(lora_B), lora_rank, float(lora_scale), _ptr(dA), _ptr(dB),
+                                        _ptr(workspace),
+                                        0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                        _stream()))
 
 
 def linear_bwd_dx_acc(dY, Wq_packed, delta_w, c_in, c_out, Gq, delta_g, acc):

@@ -56,6 +56,29 @@ BwdWs ws_bwd(int64_t t, int64_t c_out, int32_t r) {
     return w;
 }
 
+struct GradWs { size_t t1_hi, t1_lo, t2_hi, t2_lo, p1_hi, p1_lo, p2_hi, p2_lo, part_a, part_b, total; };
+GradWs ws_grad(int64_t t, int64_t c_in, int64_t c_out, int32_t r) {
+    GradWs w{};
+    const size_t tbytes = align_up((size_t)quaff::kLoraParts * t * r * 2);
+    const size_t pbytes = align_up((size_t)((t + 31) / 32 * 32) * r * 2);
+    int nslab_a, nslab_b, rows;
+    quaff::lora_grad_plan(t, c_in, &nslab_a, &rows);
+    quaff::lora_grad_plan(t, c_out, &nslab_b, &rows);
+    size_t off = 0;
+    w.t1_hi = off; off += tbytes;
+    w.t1_lo = off; off += tbytes;
+    w.t2_hi = off; off += tbytes;
+    w.t2_lo = off; off += tbytes;
+    w.p1_hi = off; off += pbytes;
+    w.p1_lo = off; off += pbytes;
+    w.p2_hi = off; off += pbytes;
+    w.p2_lo = off; off += pbytes;
+    w.part_a = off; off += align_up((size_t)nslab_a * r * c_in * 4);
+    w.part_b = off; off += align_up((size_t)nslab_b * r * c_out * 4);
+    w.total = off;
+    return w;
+}
+
 }  // namespace
 
 extern "C" {
@@ -246,6 +269,44 @@ int quaff_linear_bwd_dx_acc(const uint16_t* dY, int64_t t, int64_t lddy, const v
     g.M = t; g.N = c_in; g.K = c_out;
     g.acc1 = acc;
     return hip_status(quaff::launch_gemm(g, true, s));
+}
+
+size_t quaff_lora_bwd_workspace_bytes(int64_t t, int64_t c_in, int64_t c_out, int32_t lora_rank) {
+    if (t <= 0 || c_in <= 0 || c_out <= 0 || lora_rank <= 0) return 0;
+    return ws_grad(t, c_in, c_out, lora_rank).total + 256;
+}
+
+int quaff_lora_bwd_weights(const uint16_t* X, int64_t ldx, const uint16_t* dY, int64_t lddy, int64_t t, int64_t c_in,
+                           int64_t c_out, const uint16_t* lora_A, const uint16_t* lora_B, int32_t lora_rank,
+                           float lora_scale, float* dA, float* dB, void* workspace, size_t workspace_bytes,
+                           void* stream) {
+    if (!X || !dY || !lora_A || !lora_B || !dA || !dB) return QUAFF_ERR_NULL;
+    if (!dims_ok(t, c_in, c_out) || !rank_ok(lora_rank) || lora_rank == 0 || ldx < c_in || lddy < c_out)
+        return QUAFF_ERR_SHAPE;
+    GradWs w = ws_grad(t, c_in, c_out, lora_rank);
+    if (!workspace || workspace_bytes < w.total) return QUAFF_ERR_WORKSPACE;
+    if (!aligned16(X) || !aligned16(dY) || !aligned16(lora_A) || !aligned16(lora_B) || !aligned16(workspace) ||
+        ldx % 8 != 0 || lddy % 8 != 0)
+        return QUAFF_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* base = static_cast<char*>(workspace);
+    auto u16 = [&](size_t off) { return reinterpret_cast<uint16_t*>(base + off); };
+    // T1 = scale dY B^T (B is [r x c_out]) and T2 = scale X A (A is [c_in x r]), as the hi/lo parts of the down-projection
+    int st = hip_status(quaff::launch_lora_down(dY, t, c_out, lddy, lora_B, true, lora_rank, lora_scale, u16(w.t1_hi),
+                                                u16(w.t1_lo), nullptr, nullptr, 0, 0, s));
+    if (st != QUAFF_OK) return st;
+    st = hip_status(quaff::launch_lora_down(X, t, c_in, ldx, lora_A, false, lora_rank, lora_scale, u16(w.t2_hi),
+                                            u16(w.t2_lo), nullptr, nullptr, 0, 0, s));
+    if (st != QUAFF_OK) return st;
+    st = hip_status(quaff::launch_lora_grad_prep(u16(w.t1_hi), u16(w.t1_lo), u16(w.p1_hi), u16(w.p1_lo), u16(w.t2_hi),
+                                                 u16(w.t2_lo), u16(w.p2_hi), u16(w.p2_lo), t, lora_rank, s));
+    if (st != QUAFF_OK) return st;
+    // dA^T [r x c_in] = T1^T X, stored transposed;  dB [r x c_out] = T2^T dY
+    st = hip_status(quaff::launch_lora_grad(X, ldx, t, c_in, u16(w.p1_hi), u16(w.p1_lo), lora_rank,
+                                            reinterpret_cast<float*>(base + w.part_a), dA, true, s));
+    if (st != QUAFF_OK) return st;
+    return hip_status(quaff::launch_lora_grad(dY, lddy, t, c_out, u16(w.p2_hi), u16(w.p2_lo), lora_rank,
+                                              reinterpret_cast<float*>(base + w.part_b), dB, false, s));
 }
 
 }  // extern "C"

@@ -39,7 +39,7 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 // ---- optional per-launch timing (see quaff_profile_* in the C ABI) ------------------------------------
-enum KernelKind { K_PREPARE = 0, K_COLMAX, K_MOMENTUM, K_QUANT, K_LORA, K_GEMM, KERNEL_KINDS };
+enum KernelKind { K_PREPARE = 0, K_COLMAX, K_MOMENTUM, K_QUANT, K_LORA, K_GEMM, K_LORA_GRAD, KERNEL_KINDS };
 class ProfScope {
 public:
     ProfScope(int kind, hipStream_t stream);
@@ -68,6 +68,17 @@ hipError_t launch_quant_act(const uint16_t* X, int64_t t, int64_t c, int64_t ldx
 hipError_t launch_lora_down(const uint16_t* X, int64_t t, int64_t c, int64_t ldx, const uint16_t* L, bool L_is_r_by_c,
                             int32_t r, float scale, uint16_t* T_hi, uint16_t* T_lo, const uint16_t* tr_src,
                             uint16_t* tr_dst, int64_t tr_rows, int64_t tr_cols, hipStream_t stream);
+
+// LoRA weight gradients (quaff_lora_grad.hip).  lora_grad_plan: how the token range is cut into slabs (workspace
+// sizing); prep: fold the hi/lo parts of two down-projections into token-contiguous [r x t_pad] pairs;
+// launch_lora_grad: out [r x c] (or [c x r] when transposed) = sum_i P[i, :]^T Q[i, :], partial [nslab x r x c] scratch.
+void lora_grad_plan(int64_t t, int64_t c, int* nslab, int* rows_per_slab);
+hipError_t launch_lora_grad_prep(const uint16_t* T1_hi, const uint16_t* T1_lo, uint16_t* Pt1_hi, uint16_t* Pt1_lo,
+                                 const uint16_t* T2_hi, const uint16_t* T2_lo, uint16_t* Pt2_hi, uint16_t* Pt2_lo,
+                                 int64_t t, int32_t r, hipStream_t stream);
+hipError_t launch_lora_grad(const uint16_t* Q, int64_t ldq, int64_t t, int64_t c, const uint16_t* Pt_hi,
+                            const uint16_t* Pt_lo, int32_t r, float* partial, float* out, bool transposed,
+                            hipStream_t stream);
 
 struct GemmArgs {
     // C[M x N] from A [M x K] int8 (lda) and B [N x K] int8 (ldb), both contraction-contiguous
