@@ -247,6 +247,37 @@ def main():
         "kernels": kernels,
     }
 
+    # ---- rows beyond the headline metric, timed on their own (not part of `value`)
+    extra = {}
+    if all(L["r"] for L in layers) and all(L["p"].backward for L in layers):
+        for L in layers:
+            p, r = L["p"], L["r"]
+            L["dA"] = torch.empty((p.c_in, r), dtype=f32, device=dev)
+            L["dB"] = torch.empty((r, p.c_out), dtype=f32, device=dev)
+            L["gws"] = torch.empty(q.lora_bwd_workspace_bytes(p.t, p.c_in, p.c_out, r), dtype=i8, device=dev)
+
+        def grads(i):
+            b = i % args.batches
+            for L in layers:
+                q.lora_bwd_weights(L["X"][b], L["dY"][b], L["A"], L["B"], L["r"], L["p"].lora_scale, L["dA"], L["dB"],
+                                   L["gws"])
+        for i in range(3):
+            grads(i)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(args.steps):
+            grads(i)
+        e1.record()
+        torch.cuda.synchronize()
+        g_ms = e0.elapsed_time(e1) / args.steps
+        g_bytes = sum(2.0 * L["p"].t * (L["p"].c_in + L["p"].c_out) for L in layers)
+        extra["lora_weight_grads"] = {
+            "ms_per_step": round(g_ms, 5), "calls_per_step": "quaff_lora_bwd_weights per projection (dA, dB)",
+            "algorithmic_GBs": round(g_bytes / (g_ms * 1e-3) / 1e9, 1),
+            "frac_hbm_peak": round(g_bytes / (g_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "algorithmic_bytes": "X and dY read once (2 t (c_in + c_out)); the implementation reads each twice"}
+    out["beyond_headline"] = extra
+
     # measured ceilings next to the published peaks (register-only MFMA loop, streaming copy)
     mf_const, clk_const = q.microbench_mfma_i8(False)
     mf_rand, clk_rand = q.microbench_mfma_i8(True)
@@ -260,7 +291,8 @@ def main():
         # the oracle as it stands on the host cores: whole steps of the same workload (all projections, all rows),
         # repeated on successive batches until about 10 s of CPU work have been timed
         from oracle import api as orc
-        orc.set_threads(min(orc.max_threads(), 16))
+        nthreads = min(orc.max_threads(), 16)
+        orc.set_threads(nthreads)
         state = []
         for L in layers:
             p = L["p"]
@@ -297,11 +329,11 @@ def main():
         orc.linear_fwd(Xq, dx, xo, S["Wq"], S["dw"], what, dwh, X, S["A"], S["B"], p.lora_scale)
         one_secs = time.perf_counter() - t0
         one_tops = 2.0 * p.t * p.c_out * (p.c_in + S["O"].size) / one_secs / 1e12
-        orc.set_threads(min(orc.max_threads(), 16))
+        orc.set_threads(nthreads)
         out["cpu_baseline"] = {"single_thread": {"value": round(one_tops, 5), "unit": "TOPS", "cores": 1,
                                                  "seconds": round(one_secs, 2),
                                                  "sample": "forward of %s (scale update, quantize, forward)" % p.name},
-                               "value": round(ops / secs / 1e12, 5), "unit": "TOPS", "cores": orc.max_threads(),
+                               "value": round(ops / secs / 1e12, 5), "unit": "TOPS", "cores": nthreads,
                                "kind": "oracle", "seconds": round(secs, 2),
                                "sample": "%d whole step(s) of the same workload (every projection, all %d rows: scale "
                                          "update, quantize, forward, dX)" % (nsteps, layers[0]["p"].t)}

@@ -182,6 +182,23 @@ int quaff_lora_bwd_weights(const uint16_t* X, int64_t ldx, const uint16_t* dY, i
                            void* stream);
 
 /*
+ * Variant of the input gradient on the outlier channels (to be called after quaff_linear_bwd_dx on the same dY and
+ * dX).  The paper retains the outlier rows W_O of the frozen weight in full precision (Sec. 3.3) and s cancels in
+ * the true gradient (Eq. 3); this call overwrites the O columns of dX, where the quantization error of the
+ * activations concentrates, with the product on those retained rows:
+ *   dX[i, O_k] = sum_j dY[i, j] W_O[k, j] + lora_scale * sum_p (sum_j dY[i, j] B[p, j]) A[O_k, p]
+ * (bf16 MFMA on a 16-bit hi/lo split of the fp32 rows, fp32 accumulation).  All other columns are left untouched.
+ *   in    : dY [t x c_out] bf16 (lddy); O, W_O as for quaff_scale_update; lora_A, lora_B as for quaff_linear_bwd_dx
+ *   in/out: dX [t x c_in] fp32 (lddx)
+ * `workspace` must hold quaff_bwd_dx_outlier_workspace_bytes(t, c_out) bytes.  n_outlier = 0 is a no-op.
+ */
+size_t quaff_bwd_dx_outlier_workspace_bytes(int64_t t, int64_t c_out);
+int quaff_bwd_dx_outlier_exact(const uint16_t* dY, int64_t t, int64_t lddy, int64_t c_in, int64_t c_out,
+                               const int32_t* O, int32_t n_outlier, const float* W_O, const uint16_t* lora_A,
+                               const uint16_t* lora_B, int32_t lora_rank, float lora_scale, float* dX, int64_t lddx,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Optional per-launch kernel timing for benchmarks (not part of the method).  While enabled, every kernel the
  * library launches is bracketed by a pair of HIP events on the caller's stream; this perturbs end-to-end time, so
  * whole-step timing is taken with profiling off.  State is process-wide and guarded by a mutex.

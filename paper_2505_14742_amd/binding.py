@@ -36,6 +36,9 @@ SIGNATURES = {
     "quaff_lora_bwd_workspace_bytes": (_sz, [_i64, _i64, _i64, _i32]),
     "quaff_lora_bwd_weights": (C.c_int, [_vp, _i64, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _i32, _f32, _vp, _vp, _vp,
                                          _sz, _vp]),
+    "quaff_bwd_dx_outlier_workspace_bytes": (_sz, [_i64, _i64]),
+    "quaff_bwd_dx_outlier_exact": (C.c_int, [_vp, _i64, _i64, _i64, _i64, _vp, _i32, _vp, _vp, _vp, _i32, _f32, _vp,
+                                             _i64, _vp, _sz, _vp]),
     "quaff_profile_enable": (C.c_int, [C.c_int]),
     "quaff_profile_collect": (_i64, []),
     "quaff_profile_launch": (C.c_int, [_i64, C.POINTER(C.c_int), C.POINTER(C.c_float)]),
@@ -162,6 +165,20 @@ def lora_bwd_weights(X, dY, lora_A, lora_B, lora_rank, lora_scale, dA, dB, works
                                         _ptr(workspace),
                                         0 if workspace is None else workspace.numel() * workspace.element_size(),
                                         _stream()))
+
+
+def bwd_dx_outlier_workspace_bytes(t, c_out) -> int:
+    return int(lib().quaff_bwd_dx_outlier_workspace_bytes(t, c_out))
+
+
+def bwd_dx_outlier_exact(dY, c_in, O, W_O, lora_A, lora_B, lora_rank, lora_scale, dX, workspace):
+    t, c_out = dY.shape[0], dY.shape[1]
+    n = 0 if O is None else O.numel()
+    _check(lib().quaff_bwd_dx_outlier_exact(_ptr(dY), t, dY.stride(0), c_in, c_out, _ptr(O), n, _ptr(W_O),
+                                            _ptr(lora_A), _ptr(lora_B), lora_rank, float(lora_scale), _ptr(dX),
+                                            dX.stride(0), _ptr(workspace),
+                                            0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                            _stream()))
 
 
 def linear_bwd_dx_acc(dY, Wq_packed, delta_w, c_in, c_out, Gq, delta_g, acc):

@@ -309,4 +309,29 @@ int quaff_lora_bwd_weights(const uint16_t* X, int64_t ldx, const uint16_t* dY, i
                                               reinterpret_cast<float*>(base + w.part_b), dB, false, s));
 }
 
+size_t quaff_bwd_dx_outlier_workspace_bytes(int64_t t, int64_t c_out) {
+    if (t <= 0 || c_out <= 0) return 0;
+    return align_up((size_t)64 * c_out * 2) + 2 * align_up((size_t)quaff::kLoraParts * t * 64 * 2) + 256;
+}
+
+int quaff_bwd_dx_outlier_exact(const uint16_t* dY, int64_t t, int64_t lddy, int64_t c_in, int64_t c_out,
+                               const int32_t* O, int32_t n_outlier, const float* W_O, const uint16_t* lora_A,
+                               const uint16_t* lora_B, int32_t lora_rank, float lora_scale, float* dX, int64_t lddx,
+                               void* workspace, size_t workspace_bytes, void* stream) {
+    if (n_outlier == 0) return dims_ok(t, c_in, c_out) ? QUAFF_OK : QUAFF_ERR_SHAPE;
+    if (!dY || !O || !W_O || !dX) return QUAFF_ERR_NULL;
+    if (lora_rank > 0 && (!lora_A || !lora_B)) return QUAFF_ERR_NULL;
+    if (!dims_ok(t, c_in, c_out) || !rank_ok(lora_rank) || n_outlier < 0 || n_outlier > c_in || lddy < c_out ||
+        lddx < c_in)
+        return QUAFF_ERR_SHAPE;
+    const size_t lbytes = align_up((size_t)64 * c_out * 2), tbytes = align_up((size_t)quaff::kLoraParts * t * 64 * 2);
+    if (!workspace || workspace_bytes < lbytes + 2 * tbytes) return QUAFF_ERR_WORKSPACE;
+    if (!aligned16(dY) || !aligned16(workspace) || lddy % 8 != 0) return QUAFF_ERR_ALIGN;
+    char* base = static_cast<char*>(workspace);
+    return hip_status(quaff::launch_outlier_grad(
+        dY, t, lddy, c_out, O, n_outlier, W_O, lora_A, lora_B, lora_rank, lora_scale, dX, lddx,
+        reinterpret_cast<uint16_t*>(base), reinterpret_cast<uint16_t*>(base + lbytes),
+        reinterpret_cast<uint16_t*>(base + lbytes + tbytes), static_cast<hipStream_t>(stream)));
+}
+
 }  // extern "C"

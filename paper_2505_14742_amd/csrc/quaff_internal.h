@@ -39,7 +39,7 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 // ---- optional per-launch timing (see quaff_profile_* in the C ABI) ------------------------------------
-enum KernelKind { K_PREPARE = 0, K_COLMAX, K_MOMENTUM, K_QUANT, K_LORA, K_GEMM, K_LORA_GRAD, KERNEL_KINDS };
+enum KernelKind { K_PREPARE = 0, K_COLMAX, K_MOMENTUM, K_QUANT, K_LORA, K_GEMM, K_LORA_GRAD, K_OUTLIER_GRAD, KERNEL_KINDS };
 class ProfScope {
 public:
     ProfScope(int kind, hipStream_t stream);
@@ -79,6 +79,13 @@ hipError_t launch_lora_grad_prep(const uint16_t* T1_hi, const uint16_t* T1_lo, u
 hipError_t launch_lora_grad(const uint16_t* Q, int64_t ldq, int64_t t, int64_t c, const uint16_t* Pt_hi,
                             const uint16_t* Pt_lo, int32_t r, float* partial, float* out, bool transposed,
                             hipStream_t stream);
+
+// Full-precision dX on the outlier channels (quaff_outlier_grad.hip).  Scratch: L [64 x c_out] bf16,
+// T_hi / T_lo [kLoraParts x t x 64] bf16.
+hipError_t launch_outlier_grad(const uint16_t* dY, int64_t t, int64_t lddy, int64_t c_out, const int32_t* O, int32_t n,
+                               const float* W_O, const uint16_t* lora_A, const uint16_t* lora_B, int32_t r, float scale,
+                               float* dX, int64_t lddx, uint16_t* L, uint16_t* T_hi, uint16_t* T_lo,
+                               hipStream_t stream);
 
 struct GemmArgs {
     // C[M x N] from A [M x K] int8 (lda) and B [N x K] int8 (ldb), both contraction-contiguous
