@@ -20,6 +20,7 @@ def lib():
         _lib.oracle_linear_fwd.restype = C.c_int
         _lib.oracle_linear_bwd_dx.restype = C.c_int
         _lib.oracle_max_threads.restype = C.c_int
+        _lib.oracle_select_outliers.restype = C.c_int32
     return _lib
 
 
@@ -206,3 +207,21 @@ def bwd_dx_outlier_cols(dY, O, W_O, Wq=None, delta_w=None, what_int=None, delta_
         _p(_c(delta_what, np.float32)) if want_ste else None, _p(_c(colscale, np.float32)) if want_ste else None,
         _p(A), _p(B), i32(r), f32(lora_scale), _p(exact), _p(ste))
     return exact, ste
+
+
+def outlier_criterion(X, offsets, ratio=100.0):
+    """Eq. 6: xi [c_in] int32 for calibration samples stored one after the other (offsets [n_samples + 1])."""
+    X = _c(X, np.uint16)
+    offsets = _c(offsets, np.int64)
+    c_in = X.shape[1]
+    xi = np.empty(c_in, np.int32)
+    lib().oracle_outlier_criterion(_p(X), i64(c_in), i64(c_in), _p(offsets), i32(offsets.size - 1),
+                                   C.c_double(ratio), _p(xi))
+    return xi
+
+
+def select_outliers(xi, budget):
+    xi = _c(xi, np.int32)
+    O = np.empty(max(budget, 1), np.int32)
+    n = lib().oracle_select_outliers(_p(xi), i64(xi.size), i32(budget), _p(O))
+    return O[:n].copy()

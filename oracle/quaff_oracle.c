@@ -444,6 +444,56 @@ void oracle_bwd_dx_outlier_cols(const uint16_t* dY, int64_t t, int64_t c_out, in
     }
 }
 
+/* ------------------------------------------------------------------------
+ * Outlier-channel identification on calibration data (Eq. 6, Sec. 3.3):
+ *   xi_o = number of calibration samples i with  max_rows |X^i[:, o]| > ratio * mean(|X^i|)
+ * X holds the samples one after the other: sample i is rows offsets[i] .. offsets[i+1]-1 of X [.. x c_in].
+ * The mean is over all elements of the sample.  Reading: the comparison is strict and is made in fp64 with
+ * mean = (fp64 sum of |x|) / count; the paper uses ratio = 100.  An empty sample flags nothing.
+ * Out: xi [c_in] (int32).
+ * ---------------------------------------------------------------------- */
+void oracle_outlier_criterion(const uint16_t* X, int64_t ldx, int64_t c_in, const int64_t* offsets, int32_t n_samples,
+                              double ratio, int32_t* xi) {
+    for (int64_t o = 0; o < c_in; ++o) xi[o] = 0;
+    float* colmax = (float*)malloc(sizeof(float) * (size_t)c_in);
+    for (int32_t i = 0; i < n_samples; ++i) {
+        const int64_t r0 = offsets[i], r1 = offsets[i + 1];
+        if (r1 <= r0) continue;
+        double sum = 0.0;
+        for (int64_t o = 0; o < c_in; ++o) colmax[o] = 0.0f;
+        for (int64_t row = r0; row < r1; ++row)
+            for (int64_t o = 0; o < c_in; ++o) {
+                float a = fabsf(bf16_to_f32(X[row * ldx + o]));
+                sum += (double)a;
+                if (a > colmax[o]) colmax[o] = a;
+            }
+        const double mean = sum / ((double)(r1 - r0) * (double)c_in);
+        const double thr = ratio * mean;
+        for (int64_t o = 0; o < c_in; ++o)
+            if ((double)colmax[o] > thr) xi[o] += 1;
+    }
+    free(colmax);
+}
+
+/* Selection of O from xi (Sec. 3.3: "selecting outlier channels based on xi_o", within a per-layer budget).
+ * Reading: the `budget` channels with the largest xi, ties to the lower channel index, channels that were never
+ * flagged (xi = 0) excluded; O is returned in ascending channel order.  Returns |O|. */
+int32_t oracle_select_outliers(const int32_t* xi, int64_t c_in, int32_t budget, int32_t* O) {
+    int32_t n = 0;
+    char* taken = (char*)calloc((size_t)c_in, 1);
+    for (int32_t pick = 0; pick < budget; ++pick) {
+        int64_t best = -1;
+        for (int64_t o = 0; o < c_in; ++o)
+            if (!taken[o] && xi[o] > 0 && (best < 0 || xi[o] > xi[best])) best = o;
+        if (best < 0) break;
+        taken[best] = 1;
+    }
+    for (int64_t o = 0; o < c_in; ++o)
+        if (taken[o]) O[n++] = (int32_t)o;
+    free(taken);
+    return n;
+}
+
 /* thread control for the row-parallel loops (rows are independent in every step but the column max) */
 #ifdef _OPENMP
 #include <omp.h>

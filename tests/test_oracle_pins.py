@@ -511,6 +511,71 @@ def test_outlier_column_gradient_forms():
     assert rel(exact0, G64 @ W.astype(np.float64)[O].T) < 1e-13
 
 
+# ------------------------------------------------------------------ P15: outlier-channel identification (Eq. 6)
+def test_outlier_criterion_threshold_invariants_and_selection():
+    # strictness at the threshold, by construction: one row [M, 1 x 198]; mean = (M + 198) / 199
+    row = np.ones((1, 199), np.float32)
+    row[0, 0] = 200.0                                   # 200 = 100 * mean exactly: not an outlier
+    assert orc.outlier_criterion(bf(row).reshape(1, 199), [0, 1]).sum() == 0
+    row[0, 0] = 201.0                                   # 201 > 100 * (399 / 199)
+    xi = orc.outlier_criterion(bf(row).reshape(1, 199), [0, 1])
+    assert xi[0] == 1 and xi[1:].sum() == 0
+    # hand-built calibration set: 4 samples of different lengths, spikes planted per sample
+    rng = np.random.default_rng(11)
+    lens = [5, 9, 1, 12]
+    offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    K = 64
+    x = rng.uniform(0.5, 1.5, (sum(lens), K)).astype(np.float32) * rng.choice([-1, 1], (sum(lens), K))
+    spikes = {0: [3, 17], 1: [17], 2: [], 3: [3, 17, 40]}
+    for i, chans in spikes.items():
+        for c in chans:
+            x[offs[i] + (i % lens[i]), c] = -500.0 if c == 17 else 400.0
+    xb = bf(x).reshape(x.shape)
+    xi = orc.outlier_criterion(xb, offs)
+    want = np.zeros(K, np.int32)
+    for chans in spikes.values():
+        want[chans] += 1
+    assert np.array_equal(xi, want)
+    # independent numpy statement of Eq. 6
+    xa = np.abs(f32(xb).astype(np.float64))
+    ref = np.zeros(K, np.int32)
+    for i in range(len(lens)):
+        blk = xa[offs[i]:offs[i + 1]]
+        ref += (blk.max(axis=0) > 100.0 * blk.mean()).astype(np.int32)
+    assert np.array_equal(xi, ref)
+    # invariants: per-sample power-of-two rescaling and row order within a sample do not matter; xi <= samples
+    x2 = x.copy()
+    for i, e in enumerate([3, -2, 5, 0]):
+        x2[offs[i]:offs[i + 1]] *= np.float32(2.0 ** e)
+        x2[offs[i]:offs[i + 1]] = x2[offs[i]:offs[i + 1]][::-1]
+    assert np.array_equal(orc.outlier_criterion(bf(x2).reshape(x.shape), offs), xi)
+    assert xi.max() <= len(lens)
+    # a different ratio moves the threshold: with ratio 1000 nothing is flagged
+    assert orc.outlier_criterion(xb, offs, ratio=1000.0).sum() == 0
+    # selection: largest xi first, ties to the lower index, never-flagged channels excluded, ascending output
+    assert np.array_equal(orc.select_outliers(xi, 1), [17])
+    assert np.array_equal(orc.select_outliers(xi, 2), [3, 17])
+    assert np.array_equal(orc.select_outliers(xi, 3), [3, 17, 40])
+    assert np.array_equal(orc.select_outliers(xi, 10), [3, 17, 40])
+    tie = np.array([0, 2, 5, 2, 0, 2, 5], np.int32)
+    order = np.lexsort((np.arange(tie.size), -tie))          # independent: sort by (-xi, index)
+    for k in range(0, 8):
+        pick = np.sort([o for o in order[:k] if tie[o] > 0])
+        assert np.array_equal(orc.select_outliers(tie, k), pick)
+
+
+def test_outlier_criterion_recovers_planted_channels():
+    # outlier-bearing activations of the config-3 down projection recipe (x200 on 41 clustered channels)
+    p = synth.projection(3, "down")
+    planted = synth.outlier_indices(p)
+    samples, rows = 6, 32
+    X = np.concatenate([synth.activations(p, s, rows=slice(0, rows)) for s in range(samples)])
+    offs = np.arange(samples + 1, dtype=np.int64) * rows
+    xi = orc.outlier_criterion(X, offs)
+    assert np.array_equal(np.flatnonzero(xi == samples), planted)      # flagged in every sample, nothing else ever
+    assert np.array_equal(orc.select_outliers(xi, planted.size), planted)
+
+
 # ------------------------------------------------------------------ planted mistakes are caught by the pins above
 @pytest.mark.parametrize("mistake", ["transposed_w", "dropped_correction", "wrong_sign"])
 def test_pins_are_sensitive(mistake):
