@@ -199,6 +199,25 @@ int quaff_bwd_dx_outlier_exact(const uint16_t* dY, int64_t t, int64_t lddy, int6
                                void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Outlier-channel identification on calibration data (Eq. 6, Sec. 3.3) and selection of O within a budget:
+ *   xi[o] = number of samples i with  max_rows |X^i[:, o]| > ratio * mean(|X^i|)      (the paper uses ratio = 100)
+ *   O     = the `budget` channels with the largest xi (ties to the lower channel index; channels with xi = 0 are
+ *           never selected), in ascending channel order - the form every other call here expects
+ *   in : X [t_total x c_in] bf16 (ldx): the calibration samples one after the other; sample_offsets
+ *        [n_samples + 1] int64 DEVICE array, sample i = rows sample_offsets[i] .. sample_offsets[i + 1] - 1
+ *        (values outside [0, t_total] are clamped; an empty sample flags nothing); 1 <= n_samples <= 65535
+ *   out: xi [c_in] int32;  O [budget] int32 (the first *n_outlier entries are written), n_outlier device scalar
+ *        (O and n_outlier may be NULL when budget = 0: only xi is computed)
+ * The mean is over all elements of a sample; the comparison is strict and is made in fp64.
+ * `workspace` must hold quaff_calibrate_workspace_bytes(c_in, n_samples) bytes.
+ */
+size_t quaff_calibrate_workspace_bytes(int64_t c_in, int32_t n_samples);
+int quaff_calibrate_outliers(const uint16_t* X, int64_t t_total, int64_t c_in, int64_t ldx,
+                             const int64_t* sample_offsets, int32_t n_samples, double ratio, int32_t budget,
+                             int32_t* xi, int32_t* O, int32_t* n_outlier, void* workspace, size_t workspace_bytes,
+                             void* stream);
+
+/*
  * Optional per-launch kernel timing for benchmarks (not part of the method).  While enabled, every kernel the
  * library launches is bracketed by a pair of HIP events on the caller's stream; this perturbs end-to-end time, so
  * whole-step timing is taken with profiling off.  State is process-wide and guarded by a mutex.

@@ -39,6 +39,9 @@ SIGNATURES = {
     "quaff_bwd_dx_outlier_workspace_bytes": (_sz, [_i64, _i64]),
     "quaff_bwd_dx_outlier_exact": (C.c_int, [_vp, _i64, _i64, _i64, _i64, _vp, _i32, _vp, _vp, _vp, _i32, _f32, _vp,
                                              _i64, _vp, _sz, _vp]),
+    "quaff_calibrate_workspace_bytes": (_sz, [_i64, _i32]),
+    "quaff_calibrate_outliers": (C.c_int, [_vp, _i64, _i64, _i64, _vp, _i32, C.c_double, _i32, _vp, _vp, _vp, _vp, _sz,
+                                           _vp]),
     "quaff_profile_enable": (C.c_int, [C.c_int]),
     "quaff_profile_collect": (_i64, []),
     "quaff_profile_launch": (C.c_int, [_i64, C.POINTER(C.c_int), C.POINTER(C.c_float)]),
@@ -179,6 +182,19 @@ def bwd_dx_outlier_exact(dY, c_in, O, W_O, lora_A, lora_B, lora_rank, lora_scale
                                             dX.stride(0), _ptr(workspace),
                                             0 if workspace is None else workspace.numel() * workspace.element_size(),
                                             _stream()))
+
+
+def calibrate_workspace_bytes(c_in, n_samples) -> int:
+    return int(lib().quaff_calibrate_workspace_bytes(c_in, n_samples))
+
+
+def calibrate_outliers(X, sample_offsets, ratio, budget, xi, O, n_outlier, workspace):
+    t_total, c_in = X.shape[0], X.shape[1]
+    _check(lib().quaff_calibrate_outliers(_ptr(X), t_total, c_in, X.stride(0), _ptr(sample_offsets),
+                                          sample_offsets.numel() - 1, float(ratio), budget, _ptr(xi), _ptr(O),
+                                          _ptr(n_outlier), _ptr(workspace),
+                                          0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                          _stream()))
 
 
 def linear_bwd_dx_acc(dY, Wq_packed, delta_w, c_in, c_out, Gq, delta_g, acc):

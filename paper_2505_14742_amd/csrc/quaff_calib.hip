@@ -1,0 +1,149 @@
+// Outlier-channel identification on calibration data (Eq. 6 of the paper, Sec. 3.3) and budgeted selection of O.
+//   xi_o = number of calibration samples i with  max_rows |X^i[:, o]| > ratio * mean(|X^i|)       (ratio = 100)
+// Three launches:
+//   calib_sample_kernel   one workgroup per (2048-column chunk, sample): streams the sample's rows once (HBM-bound),
+//                         keeps the running column maxima in registers (bf16 magnitudes compare as integers) and
+//                         the sum of magnitudes in fp64;
+//   calib_count_kernel    thresholds ratio * mean per sample (fp64, chunk sums added in a fixed order), then one
+//                         thread per channel counts the samples that exceed theirs;
+//   calib_select_kernel   one workgroup ranks the channels by (xi descending, index ascending), keeps the first
+//                         `budget` with xi > 0 and writes them in ascending channel order.
+// The comparison that decides a count is made in fp64 on both sides of the parity test; the fp64 sum of a few
+// million bf16 magnitudes is exact or within an ulp whatever the order, so a decision could only differ for a
+// column maximum within 1e-15 (relative) of the threshold.
+#include "quaff_internal.h"
+
+namespace quaff {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kCalibCols = 2048;   // columns per workgroup: 256 threads x 8
+
+__global__ void __launch_bounds__(256)
+calib_sample_kernel(const uint16_t* __restrict__ X, int64_t ldx, int64_t c_in, int64_t t_total,
+                    const int64_t* __restrict__ offsets, uint16_t* __restrict__ colmax, double* __restrict__ part_sum) {
+    __shared__ double red[256];
+    const int sample = blockIdx.y, nchunk = gridDim.x;
+    int64_t r0 = offsets[sample], r1 = offsets[sample + 1];
+    r0 = r0 < 0 ? 0 : r0;                      // offsets are the caller's: never read outside X whatever they hold
+    r1 = r1 > t_total ? t_total : r1;
+    const int64_t col = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
+    const bool live = col < c_in;
+    uint32_t mx[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    double sum = 0.0;
+    if (live) {
+        const uint16_t* src = X + col;
+        for (int64_t row = r0; row < r1; row += 4) {   // four independent loads in flight
+            u32x4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                int64_t rr = row + u < r1 ? row + u : r1 - 1;
+                v[u] = *reinterpret_cast<const u32x4*>(src + rr * ldx);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (row + u >= r1) continue;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    uint32_t lo = v[u][w] & 0x7FFFu, hi = (v[u][w] >> 16) & 0x7FFFu;
+                    mx[2 * w] = lo > mx[2 * w] ? lo : mx[2 * w];
+                    mx[2 * w + 1] = hi > mx[2 * w + 1] ? hi : mx[2 * w + 1];
+                    sum += (double)__uint_as_float(lo << 16);
+                    sum += (double)__uint_as_float(hi << 16);
+                }
+            }
+        }
+        u32x4 out;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) out[w] = mx[2 * w] | (mx[2 * w + 1] << 16);
+        *reinterpret_cast<u32x4*>(colmax + (int64_t)sample * c_in + col) = out;
+    }
+    red[threadIdx.x] = sum;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {           // fixed-order tree
+        if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) part_sum[(int64_t)sample * nchunk + blockIdx.x] = red[0];
+}
+
+constexpr int kCalibTile = 2048;   // samples whose thresholds are held in LDS at a time
+
+__global__ void __launch_bounds__(256)
+calib_count_kernel(const uint16_t* __restrict__ colmax, const double* __restrict__ part_sum, int nchunk,
+                   const int64_t* __restrict__ offsets, int64_t t_total, int n_samples, int64_t c_in, double ratio,
+                   int32_t* __restrict__ xi) {
+    __shared__ double thr[kCalibTile];
+    const int64_t o = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    int count = 0;
+    for (int s0 = 0; s0 < n_samples; s0 += kCalibTile) {
+        const int ns = n_samples - s0 < kCalibTile ? n_samples - s0 : kCalibTile;
+        __syncthreads();
+        for (int i = threadIdx.x; i < ns; i += 256) {
+            int64_t r0 = offsets[s0 + i], r1 = offsets[s0 + i + 1];
+            r0 = r0 < 0 ? 0 : r0;
+            r1 = r1 > t_total ? t_total : r1;
+            double sum = 0.0;
+            for (int ch = 0; ch < nchunk; ++ch) sum += part_sum[(int64_t)(s0 + i) * nchunk + ch];
+            // an empty sample flags nothing
+            thr[i] = r1 > r0 ? ratio * (sum / ((double)(r1 - r0) * (double)c_in)) : __builtin_huge_val();
+        }
+        __syncthreads();
+        if (o < c_in)
+            for (int i = 0; i < ns; ++i) {
+                double m = (double)bf16_bits_to_f32(colmax[(int64_t)(s0 + i) * c_in + o]);
+                count += m > thr[i] ? 1 : 0;
+            }
+    }
+    if (o < c_in) xi[o] = count;
+}
+
+__global__ void __launch_bounds__(1024)
+calib_select_kernel(const int32_t* __restrict__ xi, int c_in, int budget, int32_t* __restrict__ O,
+                    int32_t* __restrict__ n_out, volatile uint8_t* sel) {
+    __shared__ int total;
+    if (threadIdx.x == 0) total = 0;
+    __syncthreads();
+    for (int o = threadIdx.x; o < c_in; o += 1024) {
+        const int x = xi[o];
+        int rank = 0;
+        for (int q = 0; q < c_in; ++q) {
+            const int y = xi[q];
+            rank += (y > x || (y == x && q < o)) ? 1 : 0;
+        }
+        const bool s = x > 0 && rank < budget;
+        sel[o] = s ? 1 : 0;
+        if (s) atomicAdd(&total, 1);
+    }
+    __threadfence_block();
+    __syncthreads();   // sel is accessed as volatile: after the barrier every thread sees the whole workgroup's flags
+    for (int o = threadIdx.x; o < c_in; o += 1024) {
+        if (!sel[o]) continue;
+        int pos = 0;
+        for (int q = 0; q < o; ++q) pos += sel[q];
+        O[pos] = o;
+    }
+    if (threadIdx.x == 0) *n_out = total;
+}
+
+hipError_t launch_calibrate(const uint16_t* X, int64_t ldx, int64_t c_in, int64_t t_total, const int64_t* offsets,
+                            int32_t n_samples, double ratio, int32_t budget, int32_t* xi, int32_t* O, int32_t* n_out,
+                            uint16_t* colmax, double* part_sum, uint8_t* sel, hipStream_t stream) {
+    ProfScope prof(K_CALIB, stream);
+    const int nchunk = (int)((c_in + kCalibCols - 1) / kCalibCols);
+    hipLaunchKernelGGL(calib_sample_kernel, dim3(nchunk, n_samples), dim3(256), 0, stream, X, ldx, c_in, t_total,
+                       offsets, colmax, part_sum);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(calib_count_kernel, dim3((unsigned)((c_in + 255) / 256)), dim3(256), 0, stream, colmax, part_sum,
+                       nchunk, offsets, t_total, n_samples, c_in, ratio, xi);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (O) {
+        hipLaunchKernelGGL(calib_select_kernel, dim3(1), dim3(1024), 0, stream, xi, (int)c_in, budget, O, n_out, sel);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
+}  // namespace quaff

@@ -39,7 +39,7 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 // ---- optional per-launch timing (see quaff_profile_* in the C ABI) ------------------------------------
-enum KernelKind { K_PREPARE = 0, K_COLMAX, K_MOMENTUM, K_QUANT, K_LORA, K_GEMM, K_LORA_GRAD, K_OUTLIER_GRAD, KERNEL_KINDS };
+enum KernelKind { K_PREPARE = 0, K_COLMAX, K_MOMENTUM, K_QUANT, K_LORA, K_GEMM, K_LORA_GRAD, K_OUTLIER_GRAD, K_CALIB, KERNEL_KINDS };
 class ProfScope {
 public:
     ProfScope(int kind, hipStream_t stream);
@@ -86,6 +86,12 @@ hipError_t launch_outlier_grad(const uint16_t* dY, int64_t t, int64_t lddy, int6
                                const float* W_O, const uint16_t* lora_A, const uint16_t* lora_B, int32_t r, float scale,
                                float* dX, int64_t lddx, uint16_t* L, uint16_t* T_hi, uint16_t* T_lo,
                                hipStream_t stream);
+
+// Outlier-channel identification (quaff_calib.hip).  Scratch: colmax [n_samples x c_in] bf16 magnitudes, part_sum
+// [n_samples x ceil(c_in / 2048)] fp64, sel [c_in] bytes.
+hipError_t launch_calibrate(const uint16_t* X, int64_t ldx, int64_t c_in, int64_t t_total, const int64_t* offsets,
+                            int32_t n_samples, double ratio, int32_t budget, int32_t* xi, int32_t* O, int32_t* n_out,
+                            uint16_t* colmax, double* part_sum, uint8_t* sel, hipStream_t stream);
 
 struct GemmArgs {
     // C[M x N] from A [M x K] int8 (lda) and B [N x K] int8 (ldb), both contraction-contiguous
