@@ -276,6 +276,49 @@ def main():
             "algorithmic_GBs": round(g_bytes / (g_ms * 1e-3) / 1e9, 1),
             "frac_hbm_peak": round(g_bytes / (g_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "algorithmic_bytes": "X and dY read once (2 t (c_in + c_out)); the implementation reads each twice"}
+    if all(L["n"] for L in layers) and all(L["p"].backward for L in layers):
+        for L in layers:
+            L["ows"] = torch.empty(q.bwd_dx_outlier_workspace_bytes(L["p"].t, L["p"].c_out), dtype=i8, device=dev)
+
+        def exact_cols(i):
+            b = i % args.batches
+            for L in layers:
+                q.bwd_dx_outlier_exact(L["dY"][b], L["p"].c_in, L["O"], L["W_O"], L["A"], L["B"], L["r"],
+                                       L["p"].lora_scale, L["dX"][b], L["ows"])
+        for i in range(3):
+            exact_cols(i)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(args.steps):
+            exact_cols(i)
+        e1.record()
+        torch.cuda.synchronize()
+        extra["exact_dx_on_outlier_channels"] = {
+            "ms_per_step": round(e0.elapsed_time(e1) / args.steps, 5),
+            "calls_per_step": "quaff_bwd_dx_outlier_exact per projection (after quaff_linear_bwd_dx)"}
+    # outlier identification (Eq. 6) on 32 calibration samples of 512 tokens of the first projection's recipe
+    p0 = layers[0]["p"]
+    ns, rows = 32, 512
+    Xc = torch.cat([layers[0]["X"][b % args.batches][:rows] for b in range(ns)]).contiguous()
+    offs = torch.arange(ns + 1, dtype=torch.int64, device=dev) * rows
+    xi = torch.empty(p0.c_in, dtype=torch.int32, device=dev)
+    Oc = torch.empty(max(layers[0]["n"], 1), dtype=torch.int32, device=dev)
+    nc = torch.empty(1, dtype=torch.int32, device=dev)
+    cws = torch.empty(q.calibrate_workspace_bytes(p0.c_in, ns), dtype=i8, device=dev)
+    for i in range(3):
+        q.calibrate_outliers(Xc, offs, 100.0, Oc.numel(), xi, Oc, nc, cws)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(10):
+        q.calibrate_outliers(Xc, offs, 100.0, Oc.numel(), xi, Oc, nc, cws)
+    e1.record()
+    torch.cuda.synchronize()
+    c_ms = e0.elapsed_time(e1) / 10
+    extra["outlier_identification"] = {
+        "ms_per_call": round(c_ms, 5), "workload": "%d samples x %d tokens x %d channels, budget %d" % (
+            ns, rows, p0.c_in, Oc.numel()),
+        "algorithmic_GBs": round(2.0 * ns * rows * p0.c_in / (c_ms * 1e-3) / 1e9, 1),
+        "channels_selected": int(nc.item())}
     out["beyond_headline"] = extra
 
     # measured ceilings next to the published peaks (register-only MFMA loop, streaming copy)

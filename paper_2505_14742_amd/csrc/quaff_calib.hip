@@ -1,13 +1,13 @@
 // Outlier-channel identification on calibration data (Eq. 6 of the paper, Sec. 3.3) and budgeted selection of O.
 //   xi_o = number of calibration samples i with  max_rows |X^i[:, o]| > ratio * mean(|X^i|)       (ratio = 100)
-// Three launches:
-//   calib_sample_kernel   one workgroup per (2048-column chunk, sample): streams the sample's rows once (HBM-bound),
+// Four launches:
+//   calib_sample_kernel   one workgroup per (2048-column chunk, sample, row slab): streams its rows once (HBM-bound),
 //                         keeps the running column maxima in registers (bf16 magnitudes compare as integers) and
 //                         the sum of magnitudes in fp64;
 //   calib_count_kernel    thresholds ratio * mean per sample (fp64, chunk sums added in a fixed order), then one
 //                         thread per channel counts the samples that exceed theirs;
-//   calib_select_kernel   one workgroup ranks the channels by (xi descending, index ascending), keeps the first
-//                         `budget` with xi > 0 and writes them in ascending channel order.
+//   calib_rank_kernel     one thread per channel ranks it by (xi descending, index ascending) and flags the first
+//   calib_place_kernel    `budget` channels with xi > 0; the flagged channels are then written in ascending order.
 // The comparison that decides a count is made in fp64 on both sides of the parity test; the fp64 sum of a few
 // million bf16 magnitudes is exact or within an ulp whatever the order, so a decision could only differ for a
 // column maximum within 1e-15 (relative) of the threshold.
@@ -18,6 +18,7 @@ namespace quaff {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kCalibCols = 2048;   // columns per workgroup: 256 threads x 8
+constexpr int kCalibSlabs = 8;     // a sample's rows are cut into this many slabs, one workgroup each
 
 __global__ void __launch_bounds__(256)
 calib_sample_kernel(const uint16_t* __restrict__ X, int64_t ldx, int64_t c_in, int64_t t_total,
@@ -27,6 +28,12 @@ calib_sample_kernel(const uint16_t* __restrict__ X, int64_t ldx, int64_t c_in, i
     int64_t r0 = offsets[sample], r1 = offsets[sample + 1];
     r0 = r0 < 0 ? 0 : r0;                      // offsets are the caller's: never read outside X whatever they hold
     r1 = r1 > t_total ? t_total : r1;
+    {
+        const int64_t per = r1 > r0 ? (r1 - r0 + kCalibSlabs - 1) / kCalibSlabs : 0;
+        r0 += blockIdx.z * per;
+        r1 = r0 + per < r1 ? r0 + per : r1;   // may leave this slab empty (r1 <= r0)
+    }
+    const int64_t unit = (int64_t)sample * kCalibSlabs + blockIdx.z;
     const int64_t col = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
     const bool live = col < c_in;
     uint32_t mx[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -56,7 +63,7 @@ calib_sample_kernel(const uint16_t* __restrict__ X, int64_t ldx, int64_t c_in, i
         u32x4 out;
 #pragma unroll
         for (int w = 0; w < 4; ++w) out[w] = mx[2 * w] | (mx[2 * w + 1] << 16);
-        *reinterpret_cast<u32x4*>(colmax + (int64_t)sample * c_in + col) = out;
+        *reinterpret_cast<u32x4*>(colmax + unit * c_in + col) = out;
     }
     red[threadIdx.x] = sum;
     __syncthreads();
@@ -64,7 +71,7 @@ calib_sample_kernel(const uint16_t* __restrict__ X, int64_t ldx, int64_t c_in, i
         if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
         __syncthreads();
     }
-    if (threadIdx.x == 0) part_sum[(int64_t)sample * nchunk + blockIdx.x] = red[0];
+    if (threadIdx.x == 0) part_sum[unit * nchunk + blockIdx.x] = red[0];
 }
 
 constexpr int kCalibTile = 2048;   // samples whose thresholds are held in LDS at a time
@@ -84,46 +91,64 @@ calib_count_kernel(const uint16_t* __restrict__ colmax, const double* __restrict
             r0 = r0 < 0 ? 0 : r0;
             r1 = r1 > t_total ? t_total : r1;
             double sum = 0.0;
-            for (int ch = 0; ch < nchunk; ++ch) sum += part_sum[(int64_t)(s0 + i) * nchunk + ch];
+            for (int ch = 0; ch < kCalibSlabs * nchunk; ++ch) sum += part_sum[(int64_t)(s0 + i) * kCalibSlabs * nchunk + ch];
             // an empty sample flags nothing
             thr[i] = r1 > r0 ? ratio * (sum / ((double)(r1 - r0) * (double)c_in)) : __builtin_huge_val();
         }
         __syncthreads();
         if (o < c_in)
             for (int i = 0; i < ns; ++i) {
-                double m = (double)bf16_bits_to_f32(colmax[(int64_t)(s0 + i) * c_in + o]);
+                uint32_t mb = 0;
+#pragma unroll
+                for (int z = 0; z < kCalibSlabs; ++z) {
+                    uint32_t v = colmax[((int64_t)(s0 + i) * kCalibSlabs + z) * c_in + o];
+                    mb = v > mb ? v : mb;
+                }
+                double m = (double)bf16_bits_to_f32(mb);
                 count += m > thr[i] ? 1 : 0;
             }
     }
     if (o < c_in) xi[o] = count;
 }
 
-__global__ void __launch_bounds__(1024)
-calib_select_kernel(const int32_t* __restrict__ xi, int c_in, int budget, int32_t* __restrict__ O,
-                    int32_t* __restrict__ n_out, volatile uint8_t* sel) {
-    __shared__ int total;
-    if (threadIdx.x == 0) total = 0;
-    __syncthreads();
-    for (int o = threadIdx.x; o < c_in; o += 1024) {
-        const int x = xi[o];
-        int rank = 0;
-        for (int q = 0; q < c_in; ++q) {
-            const int y = xi[q];
-            rank += (y > x || (y == x && q < o)) ? 1 : 0;
+// sel[o] = 1 iff channel o is among the `budget` largest xi (ties to the lower index) and xi[o] > 0.
+// One thread per channel; xi is walked through LDS in tiles.
+__global__ void __launch_bounds__(256)
+calib_rank_kernel(const int32_t* __restrict__ xi, int c_in, int budget, uint8_t* __restrict__ sel) {
+    __shared__ int32_t tile[2048];
+    const int o = blockIdx.x * 256 + threadIdx.x;
+    const int x = o < c_in ? xi[o] : 0;
+    int rank = 0;
+    for (int q0 = 0; q0 < c_in; q0 += 2048) {
+        const int nq = c_in - q0 < 2048 ? c_in - q0 : 2048;
+        __syncthreads();
+        for (int q = threadIdx.x; q < nq; q += 256) tile[q] = xi[q0 + q];
+        __syncthreads();
+        for (int q = 0; q < nq; ++q) {
+            const int y = tile[q];
+            rank += (y > x || (y == x && q0 + q < o)) ? 1 : 0;
         }
-        const bool s = x > 0 && rank < budget;
-        sel[o] = s ? 1 : 0;
-        if (s) atomicAdd(&total, 1);
     }
-    __threadfence_block();
-    __syncthreads();   // sel is accessed as volatile: after the barrier every thread sees the whole workgroup's flags
-    for (int o = threadIdx.x; o < c_in; o += 1024) {
-        if (!sel[o]) continue;
-        int pos = 0;
-        for (int q = 0; q < o; ++q) pos += sel[q];
-        O[pos] = o;
+    if (o < c_in) sel[o] = (x > 0 && rank < budget) ? 1 : 0;
+}
+
+// O[pos] = o for the selected channels in ascending order, pos = number of selected channels below o
+__global__ void __launch_bounds__(256)
+calib_place_kernel(const uint8_t* __restrict__ sel, int c_in, int32_t* __restrict__ O, int32_t* __restrict__ n_out) {
+    __shared__ uint8_t tile[4096];
+    const int o = blockIdx.x * 256 + threadIdx.x;
+    const int last = blockIdx.x * 256 + 255 < c_in - 1 ? blockIdx.x * 256 + 255 : c_in - 1;   // highest channel here
+    int pos = 0;
+    for (int q0 = 0; q0 <= last; q0 += 4096) {
+        const int nq = c_in - q0 < 4096 ? c_in - q0 : 4096;
+        __syncthreads();
+        for (int q = threadIdx.x; q < nq; q += 256) tile[q] = sel[q0 + q];
+        __syncthreads();
+        const int lim = o - q0 < nq ? o - q0 : nq;     // channels q0 .. min(o, q0 + nq) - 1
+        for (int q = 0; q < lim; ++q) pos += tile[q];
     }
-    if (threadIdx.x == 0) *n_out = total;
+    if (o < c_in && sel[o]) O[pos] = o;
+    if (o == c_in - 1) *n_out = pos + sel[o];
 }
 
 hipError_t launch_calibrate(const uint16_t* X, int64_t ldx, int64_t c_in, int64_t t_total, const int64_t* offsets,
@@ -131,7 +156,7 @@ hipError_t launch_calibrate(const uint16_t* X, int64_t ldx, int64_t c_in, int64_
                             uint16_t* colmax, double* part_sum, uint8_t* sel, hipStream_t stream) {
     ProfScope prof(K_CALIB, stream);
     const int nchunk = (int)((c_in + kCalibCols - 1) / kCalibCols);
-    hipLaunchKernelGGL(calib_sample_kernel, dim3(nchunk, n_samples), dim3(256), 0, stream, X, ldx, c_in, t_total,
+    hipLaunchKernelGGL(calib_sample_kernel, dim3(nchunk, n_samples, kCalibSlabs), dim3(256), 0, stream, X, ldx, c_in, t_total,
                        offsets, colmax, part_sum);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -140,7 +165,11 @@ hipError_t launch_calibrate(const uint16_t* X, int64_t ldx, int64_t c_in, int64_
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (O) {
-        hipLaunchKernelGGL(calib_select_kernel, dim3(1), dim3(1024), 0, stream, xi, (int)c_in, budget, O, n_out, sel);
+        const unsigned nb = (unsigned)((c_in + 255) / 256);
+        hipLaunchKernelGGL(calib_rank_kernel, dim3(nb), dim3(256), 0, stream, xi, (int)c_in, budget, sel);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(calib_place_kernel, dim3(nb), dim3(256), 0, stream, sel, (int)c_in, O, n_out);
         e = hipGetLastError();
     }
     return e;

@@ -87,8 +87,8 @@ hipError_t launch_outlier_grad(const uint16_t* dY, int64_t t, int64_t lddy, int6
                                float* dX, int64_t lddx, uint16_t* L, uint16_t* T_hi, uint16_t* T_lo,
                                hipStream_t stream);
 
-// Outlier-channel identification (quaff_calib.hip).  Scratch: colmax [n_samples x c_in] bf16 magnitudes, part_sum
-// [n_samples x ceil(c_in / 2048)] fp64, sel [c_in] bytes.
+// Outlier-channel identification (quaff_calib.hip).  Scratch: colmax [n_samples x 8 x c_in] bf16 magnitudes, part_sum
+// [n_samples x 8 x ceil(c_in / 2048)] fp64 (8 row slabs per sample), sel [c_in] bytes.
 hipError_t launch_calibrate(const uint16_t* X, int64_t ldx, int64_t c_in, int64_t t_total, const int64_t* offsets,
                             int32_t n_samples, double ratio, int32_t budget, int32_t* xi, int32_t* O, int32_t* n_out,
                             uint16_t* colmax, double* part_sum, uint8_t* sel, hipStream_t stream);
