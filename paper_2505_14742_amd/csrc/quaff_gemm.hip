@@ -46,16 +46,13 @@ static hipError_t launch_dma(const GemmArgs& g, bool dump, hipStream_t stream) {
         hipLaunchKernelGGL(k, grid, block, C::LDS_BYTES, stream, g, tm);
     } else if ((int64_t)(g.K2 / 64) * C::K2_PLANES_BYTES <= C::EPI_LIMIT) {
         // the epilogue operands are staged through the idle LDS ring
-        auto k = gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, false, MINB, PAIR, true>;
+        auto k = g.accumulate ? gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, false, MINB, PAIR, true, true>
+                              : gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, false, MINB, PAIR, true, false>;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_ALLOC);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, block, C::LDS_ALLOC, stream, g, tm);
     } else {
-        // very wide second product: epilogue operands come straight from global memory
-        auto k = gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, false, MINB, PAIR, false>;
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(k, grid, block, C::LDS_BYTES, stream, g, tm);
+        return hipErrorInvalidValue;   // launch_gemm splits such a product into two launches
     }
     return hipGetLastError();
 }
@@ -89,8 +86,31 @@ int choose_tile(int64_t M, int64_t N) {
 }
 }  // namespace
 
+static hipError_t launch_gemm_one(const GemmArgs& g, bool dump_acc, hipStream_t stream);
+
 hipError_t launch_gemm(const GemmArgs& g, bool dump_acc, hipStream_t stream) {
     ProfScope prof(K_GEMM, stream);
+    // A second product too wide for the epilogue's LDS staging (more than two to four 64-wide outlier slices,
+    // depending on the tile shape) runs as a launch of its own that writes row_scale * acc2 * col_scale2, and the
+    // main product then accumulates onto it: one extra write and read of the output instead of a slow epilogue.
+    const bool main_fast = g.K % 64 == 0 && g.M * g.lda < ((int64_t)1 << 32) && g.N * g.ldb < ((int64_t)1 << 32);
+    if (!dump_acc && g.K2 > 128 && main_fast) {
+        GemmArgs c2{};
+        c2.A = g.A2; c2.lda = g.K2; c2.B = g.B2; c2.ldb = g.K2;
+        c2.M = g.M; c2.N = g.N; c2.K = g.K2;
+        c2.row_scale = g.row_scale; c2.col_scale = g.col_scale2;
+        c2.C = g.C; c2.ldc = g.ldc;
+        hipError_t e = launch_gemm_one(c2, false, stream);
+        if (e != hipSuccess) return e;
+        GemmArgs m = g;
+        m.K2 = 0; m.A2 = nullptr; m.B2 = nullptr; m.col_scale2 = nullptr;
+        m.accumulate = 1;
+        return launch_gemm_one(m, false, stream);
+    }
+    return launch_gemm_one(g, dump_acc, stream);
+}
+
+hipError_t launch_gemm_one(const GemmArgs& g, bool dump_acc, hipStream_t stream) {
     const int64_t lim32 = (int64_t)1 << 32;
     const bool dma_ok = g.K % 64 == 0 && g.M * g.lda < lim32 && g.N * g.ldb < lim32;
     if (!dma_ok) return launch_generic<128, 128, 64, 2, 2>(g, dump_acc, stream);

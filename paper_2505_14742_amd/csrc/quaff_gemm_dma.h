@@ -227,8 +227,8 @@ __device__ __forceinline__ void gemm_mainloop_dma2(const int8_t* __restrict__ gA
 //   phase A  acc2 = A2 B2^T per block (int32, exact); the block becomes  row_scale * (acc * cs + acc2 * cs2)  in fp32
 //   phase B  the low-rank products accumulate onto the fp32 block, 32 columns of r per staging round
 //   phase C  stores (all loads precede all stores: they share one in-order counter)
-// The caller guarantees (K2 / 64) * K2_PLANES_BYTES <= EPI_LIMIT.
-template <class C>
+// ACCUM adds what C already holds (read in phase A).  The caller guarantees (K2 / 64) * K2_PLANES_BYTES <= EPI_LIMIT.
+template <class C, bool ACCUM>
 __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (&acc)[C::TM][C::TN],
                                                      lds_i8* __restrict__ dma, const lds_i8* __restrict__ rd,
                                                      int64_t m0, int64_t n0, int wm, int wn, int wave, int lane) {
@@ -333,10 +333,23 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
                                                                  frag(off + PLANE_A, wn * C::WN + j * 32, ks * 2 + lhi),
                                                                  acc2, 0, 0, 0);
             }
+            float prev[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) prev[v] = 0.0f;
+            if constexpr (ACCUM) {
+                // this lane's 16 output elements of the block, as phase C addresses them (clamped: never stored)
+                const int64_t ib = row0 + i * 32, col = col0 + j * 32 + l32;
+                const int64_t cc = col < g.N ? col : g.N - 1;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    int64_t row = ib + (v >> 2) * 8 + lhi * 4 + (v & 3);
+                    prev[v] = g.C[(row < g.M ? row : g.M - 1) * g.ldc + cc];
+                }
+            }
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 float inner = __builtin_fmaf((float)acc[i][j][v], cs, (float)acc2[v] * cs2);
-                acc[i][j][v] = __float_as_int(rs[v >> 2][v & 3] * inner);
+                acc[i][j][v] = __float_as_int(rs[v >> 2][v & 3] * inner + prev[v]);
             }
         }
     }
@@ -396,7 +409,8 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int STAGES, bool DUMP, int MINB = 1, int PAIR = 0, bool STAGED = false>
+template <int BM, int BN, int WGM, int WGN, int STAGES, bool DUMP, int MINB = 1, int PAIR = 0, bool STAGED = false,
+          bool ACCUM = false>
 __global__ void __launch_bounds__(64 * WGM * WGN, MINB)
 gemm_i8_dma_kernel(const GemmArgs g, const TileMap tmap) {
     using C = DmaCfg<BM, BN, WGM, WGN, STAGES>;
@@ -445,7 +459,7 @@ gemm_i8_dma_kernel(const GemmArgs g, const TileMap tmap) {
         gemm_mainloop_dma<C>(g.A, g.B, voff, (int)(g.K / C::BK), lds, lds, wave, a_frag_off, b_frag_off, acc);
 
     if constexpr (STAGED && !DUMP)
-        gemm_epilogue_staged<C>(g, acc, lds, lds, m0, n0, wm, wn, wave, lane);
+        gemm_epilogue_staged<C, ACCUM>(g, acc, lds, lds, m0, n0, wm, wn, wave, lane);
     else
         gemm_epilogue<C::TM, C::TN, DUMP>(g, acc, m0 + wm * C::WM, n0 + wn * C::WN, l32, lhi);
 }

@@ -107,6 +107,8 @@ struct GemmArgs {
     // (r-contiguous); part p starts M * r elements after part p - 1
     const uint16_t* T_hi; const uint16_t* T_lo; const uint16_t* L; int32_t r;
     float* C; int64_t ldc;         // fp32 output (mode 0)
+    int32_t accumulate;            // fast kernel only: add the result to what C already holds instead of overwriting it
+                                   // (selects a separate kernel instantiation)
     int32_t* acc1; int32_t* acc2;  // int32 dumps (mode 1), dense ld = N
 };
 hipError_t launch_gemm(const GemmArgs& g, bool dump_acc, hipStream_t stream);

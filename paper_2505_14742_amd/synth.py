@@ -142,6 +142,10 @@ CONFIGS: dict[int, list[Projection]] = {
         for i, (nm, k, n) in enumerate([("q", 5120, 5120), ("k", 5120, 5120), ("v", 5120, 5120),
                                         ("o", 5120, 5120), ("gate", 5120, 13824), ("up", 5120, 13824),
                                         ("down", 13824, 5120)])],
+    # beyond the five baseline workloads: the paper's own outlier budget (Sec. "Experimental settings": up to 4 % of
+    # c_in on o_proj and 10 % on down_proj) at the Phi-3-mini shapes - the correction product and the column
+    # abs-max become first-order costs
+    6: [_phi3(6, 0, "o_proj", 3072, 3072, 123, 2), _phi3(6, 1, "down", 8192, 3072, 819, 2)],
 }
 
 

@@ -76,3 +76,9 @@ def test_config4_llama7b_layer(name):
 @pytest.mark.parametrize("name", ["q", "gate", "down"])
 def test_config5_long_sequence(name):
     _run_projection(synth.projection(5, name), range(1), prepare_check=(name == "q"))
+
+
+@pytest.mark.parametrize("name", ["o_proj", "down"])
+def test_paper_outlier_budget_workload(name):
+    """4 % / 10 % of the input channels as outliers: the wide second product runs as its own launch."""
+    _run_projection(synth.projection(6, name), range(2))
