@@ -209,7 +209,8 @@ def main():
             if L["n"]:
                 seg = len(set(int(o) // 32 for o in L["O"].cpu().tolist()))
                 useful += 2.0 * L["p"].t * L["n"]
-                fetched += 64.0 * L["p"].t * seg
+                # the library streams whole rows when the outliers touch most segments anyway (n * 64 >= c_in)
+                fetched += 2.0 * L["p"].t * L["p"].c_in if L["n"] * 64 >= L["p"].c_in else 64.0 * L["p"].t * seg
         col_ms = kinds["colmax_outlier"][0] / prof_steps
         kernels["colmax_outlier"]["useful_GBs"] = round(useful / (col_ms * 1e-3) / 1e9, 1)
         kernels["colmax_outlier"]["fetched_GBs"] = round(fetched / (col_ms * 1e-3) / 1e9, 1)
