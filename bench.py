@@ -178,29 +178,30 @@ def main():
             if ln.strip().startswith("gemm_traffic_bytes_per_launch"):
                 gemm_traffic = int(ln.split("=")[1])
     # HBM-bound kernels: algorithmic bytes / measured time
-    quant_bytes = 0.0
-    for L in layers:
-        p = L["p"]
-        quant_bytes += 3.0 * p.t * p.c_in + 4.0 * p.t + p.t * L["n_pad"]
-        if p.backward:
-            quant_bytes += 3.0 * p.t * p.c_out + 4.0 * p.t
-    quant_ms = kinds.get("quant_rows", [0.0, 1])[0] / prof_steps
-    kernels = {name: {"avg_us": round(v[0] / v[1] * 1e3, 2), "launches_per_step": v[1] // prof_steps,
-                      "us_per_step": round(v[0] / prof_steps * 1e3, 2)} for name, v in kinds.items()}
-    kernels["quant_rows"]["achieved_GBs"] = round(quant_bytes / (quant_ms * 1e-3) / 1e9, 1)
-    kernels["quant_rows"]["frac_hbm_peak"] = round(quant_bytes / (quant_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
-    # LoRA down-projection: reads the activation (or dY) and the factor once, writes the hi/lo partial sums
-    lora_bytes = 0.0
+    # forward quantizer: 2 B read + 1 B written per element; backward: one launch quantizes dY and forms dY B^T
+    quant_bytes = fused_bytes = lora_bytes = 0.0
     for L in layers:
         p, r = L["p"], L["r"]
+        quant_bytes += 3.0 * p.t * p.c_in + 4.0 * p.t + p.t * L["n_pad"]
         if r:
             lora_bytes += 2.0 * p.t * p.c_in + 2.0 * p.c_in * r + 8.0 * p.t * r + 4.0 * p.c_out * r
-            if p.backward:
-                lora_bytes += 2.0 * p.t * p.c_out + 2.0 * p.c_out * r + 8.0 * p.t * r
-    if "lora_down" in kernels and lora_bytes:
-        lora_ms = kinds["lora_down"][0] / prof_steps
-        kernels["lora_down"]["achieved_GBs"] = round(lora_bytes / (lora_ms * 1e-3) / 1e9, 1)
-        kernels["lora_down"]["frac_hbm_peak"] = round(lora_bytes / (lora_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+        if p.backward:
+            fused_bytes += 3.0 * p.t * p.c_out + 4.0 * p.t + (2.0 * p.c_out * r + 8.0 * p.t * r if r else 0.0)
+    kernels = {name: {"avg_us": round(v[0] / v[1] * 1e3, 2), "launches_per_step": v[1] // prof_steps,
+                      "us_per_step": round(v[0] / prof_steps * 1e3, 2)} for name, v in kinds.items()}
+
+    def hbm(name, nbytes):
+        if name in kernels and nbytes:
+            ms = kinds[name][0] / prof_steps
+            kernels[name]["achieved_GBs"] = round(nbytes / (ms * 1e-3) / 1e9, 1)
+            kernels[name]["frac_hbm_peak"] = round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+    if "quant_rows+lora_down" in kernels:
+        hbm("quant_rows", quant_bytes)
+        hbm("quant_rows+lora_down", fused_bytes)
+        hbm("lora_down", lora_bytes)
+    else:   # rank 0 or shapes the combined launch does not cover: separate launches in the backward pass too
+        hbm("quant_rows", quant_bytes + fused_bytes)
+        hbm("lora_down", lora_bytes)
     # column abs-max: useful bytes are the 2-byte outlier entries; what the memory system must fetch is one
     # 64-byte segment per (row, distinct segment touched by O) - counted here from the outlier positions
     if "colmax_outlier" in kernels:

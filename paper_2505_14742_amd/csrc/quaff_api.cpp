@@ -235,20 +235,32 @@ int quaff_linear_bwd_dx(const uint16_t* dY, int64_t t, int64_t lddy, const void*
     int8_t* gq = reinterpret_cast<int8_t*>(base + w.gq);
     float* dg = reinterpret_cast<float*>(base + w.dg);
     PackedWeight pw = unpack(Wq_packed, c_in, c_out);
-    int st = hip_status(quaff::launch_quant_act(dY, t, c_out, lddy, delta_w, nullptr, 0, gq, dg, nullptr, s));
-    if (st != QUAFF_OK) return st;
     quaff::GemmArgs g{};
     g.A = gq; g.lda = c_out; g.B = pw.Wn; g.ldb = c_out;
     g.M = t; g.N = c_in; g.K = c_out;
     g.row_scale = dg;
+    int st;
+    bool quantized = false;
     if (lora_rank > 0) {
         uint16_t* t_hi = reinterpret_cast<uint16_t*>(base + w.t_hi);
         uint16_t* t_lo = reinterpret_cast<uint16_t*>(base + w.t_lo);
-        // T = scale * dY B^T (B is [r x c_out], contraction-contiguous); the epilogue multiplies by A [c_in x r]
-        st = hip_status(quaff::launch_lora_down(dY, t, c_out, lddy, lora_B, true, lora_rank, lora_scale, t_hi, t_lo,
-                                                nullptr, nullptr, 0, 0, s));
-        if (st != QUAFF_OK) return st;
+        // T = scale * dY B^T (B is [r x c_out], contraction-contiguous); the epilogue multiplies by A [c_in x r].
+        // The quantizer and this down-projection both only read dY: one launch runs them side by side when it can.
+        hipError_t e = hipSuccess;
+        quantized = quaff::launch_quant_lora(dY, t, c_out, lddy, delta_w, gq, dg, lora_B, lora_rank, lora_scale, t_hi,
+                                             t_lo, s, &e);
+        if (quantized) {
+            if ((st = hip_status(e)) != QUAFF_OK) return st;
+        } else {
+            st = hip_status(quaff::launch_lora_down(dY, t, c_out, lddy, lora_B, true, lora_rank, lora_scale, t_hi,
+                                                    t_lo, nullptr, nullptr, 0, 0, s));
+            if (st != QUAFF_OK) return st;
+        }
         g.T_hi = t_hi; g.T_lo = t_lo; g.L = lora_A; g.r = lora_rank;
+    }
+    if (!quantized) {
+        st = hip_status(quaff::launch_quant_act(dY, t, c_out, lddy, delta_w, nullptr, 0, gq, dg, nullptr, s));
+        if (st != QUAFF_OK) return st;
     }
     g.C = dX; g.ldc = lddx;
     return hip_status(quaff::launch_gemm(g, false, s));

@@ -39,7 +39,7 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 // ---- optional per-launch timing (see quaff_profile_* in the C ABI) ------------------------------------
-enum KernelKind { K_PREPARE = 0, K_COLMAX, K_MOMENTUM, K_QUANT, K_LORA, K_GEMM, K_LORA_GRAD, K_OUTLIER_GRAD, K_CALIB, KERNEL_KINDS };
+enum KernelKind { K_PREPARE = 0, K_COLMAX, K_MOMENTUM, K_QUANT, K_LORA, K_GEMM, K_LORA_GRAD, K_OUTLIER_GRAD, K_CALIB, K_QUANT_LORA, KERNEL_KINDS };
 class ProfScope {
 public:
     ProfScope(int kind, hipStream_t stream);
@@ -92,6 +92,13 @@ hipError_t launch_outlier_grad(const uint16_t* dY, int64_t t, int64_t lddy, int6
 hipError_t launch_calibrate(const uint16_t* X, int64_t ldx, int64_t c_in, int64_t t_total, const int64_t* offsets,
                             int32_t n_samples, double ratio, int32_t budget, int32_t* xi, int32_t* O, int32_t* n_out,
                             uint16_t* colmax, double* part_sum, uint8_t* sel, hipStream_t stream);
+
+// Quantizer (colscale = cs, no outlier copy) and LoRA down-projection with a contraction-contiguous factor
+// L [r x c] of the same bf16 matrix X in ONE launch (quaff_quant_lora.hip).  Returns false, with nothing enqueued,
+// for shapes it does not cover; otherwise *err holds the launch status.
+bool launch_quant_lora(const uint16_t* X, int64_t t, int64_t c, int64_t ldx, const float* cs, int8_t* Xq, float* delta,
+                       const uint16_t* L_r_by_c, int32_t r, float scale, uint16_t* T_hi, uint16_t* T_lo,
+                       hipStream_t stream, hipError_t* err);
 
 struct GemmArgs {
     // C[M x N] from A [M x K] int8 (lda) and B [N x K] int8 (ldb), both contraction-contiguous

@@ -9,21 +9,9 @@
 // T is handed to the GEMM epilogue as a bf16 pair (hi + lo, 16 significant bits) so that the up-projection can
 // also run on the bf16 MFMA without losing the fp32 accumulation's accuracy.  Extra workgroups of the same launch
 // write the transposed copy of the other factor that the epilogue reads contraction-contiguous.
-#include "quaff_internal.h"
+#include "quaff_lora_body.h"
 
 namespace quaff {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-constexpr int kLoraWaves = 16;
-constexpr int kLoraUnroll = 6;   // contraction steps whose loads are issued together (latency hiding); even
-
-__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
-    uint32_t u = __float_as_uint(f);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
 
 // R16 = r / 16 column blocks of T.  L_RC: L is [r x c] (contraction-contiguous) else [c x r].
 template <int R16, bool L_RC>
@@ -31,119 +19,8 @@ __global__ void __launch_bounds__(64 * kLoraWaves)
 lora_down_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx, const uint16_t* __restrict__ L,
                  float scale, uint16_t* __restrict__ T_hi, uint16_t* __restrict__ T_lo, int row_blocks,
                  const uint16_t* __restrict__ tr_src, uint16_t* __restrict__ tr_dst, int64_t tr_rows, int64_t tr_cols) {
-    constexpr int r = R16 * 16;
-    constexpr int NT = 64 * kLoraWaves;
-    constexpr int TROW = 40;                       // padded row (in bf16) of the transposed slice: 32 + 8
-    if ((int)blockIdx.x >= row_blocks) {
-        if (blockIdx.y != 0) return;
-        // transposed copy: dst [cols x rows] <- src [rows x cols]
-        int64_t total = tr_rows * tr_cols;
-        int64_t nb = gridDim.x - row_blocks;
-        for (int64_t e = ((int64_t)blockIdx.x - row_blocks) * NT + threadIdx.x; e < total; e += nb * NT) {
-            int64_t col = e / tr_rows, row = e % tr_rows;
-            tr_dst[e] = tr_src[row * tr_cols + col];
-        }
-        return;
-    }
-    __shared__ float red[kLoraWaves][R16][64][4];
-    __shared__ __attribute__((aligned(16))) uint16_t lt[L_RC ? 1 : kLoraWaves][L_RC ? 1 : r][L_RC ? 8 : TROW];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int m = lane & 15, g = lane >> 4;
-    const int64_t row = (int64_t)blockIdx.x * 16 + m;
-    const bool live = row < t;
-    const uint16_t* xrow = X + (live ? row : 0) * ldx;
-
-    f32x4 acc[R16];
-#pragma unroll
-    for (int b = 0; b < R16; ++b) acc[b] = (f32x4){0.f, 0.f, 0.f, 0.f};
-
-    // each wavefront owns one contiguous slice of the contraction range (kw columns), walked in 32-column steps
-    // this workgroup's part of the contraction range, then this wavefront's slice of it
-    // (multiples of 64 columns = 128 bytes, so that a pair of steps reads whole cache lines, see below)
-    const int cp = ((c + kLoraParts * 64 - 1) / (kLoraParts * 64)) * 64;
-    const int cbeg = blockIdx.y * cp, cend = cbeg + cp < c ? cbeg + cp : c;
-    const int kw = ((cend - cbeg + kLoraWaves * 64 - 1) / (kLoraWaves * 64)) * 64;
-    const int kbeg = cbeg + wave * kw, kend = kbeg + kw < cend ? kbeg + kw : cend;
-    T_hi += (int64_t)blockIdx.y * t * r;
-    T_lo += (int64_t)blockIdx.y * t * r;
-    for (int kk0 = kbeg; kk0 < kend; kk0 += 32 * kLoraUnroll) {
-        u32x4 xa[kLoraUnroll], lb[kLoraUnroll][R16];
-        // all global loads of the batch first
-#pragma unroll
-        for (int u = 0; u < kLoraUnroll; ++u) {
-            // Two consecutive steps share 64 columns: lane group g takes columns 16 g .. 16 g + 7 in the even step
-            // and 16 g + 8 .. 16 g + 15 in the odd one (any assignment of contraction indices to MFMA slots is
-            // valid as long as both operands use it), so the four groups of a row read one whole 128-byte line
-            // per step pair instead of two half lines.
-            const int k0 = kk0 + (u >> 1) * 64 + (u & 1) * 8;
-            const int k = k0 + g * 16;         // this lane's eight contraction indices
-            // loads are unconditional (address clamped into the row) so that the whole batch is in flight together;
-            // a step past the end contributes zero because its x fragment is cleared
-            const int kc = k < kend ? k : c - 8;
-            xa[u] = *reinterpret_cast<const u32x4*>(xrow + kc);
-            if (!(live && k < kend)) xa[u] = (u32x4){0, 0, 0, 0};
-            if (L_RC) {
-#pragma unroll
-                for (int b = 0; b < R16; ++b)
-                    lb[u][b] = *reinterpret_cast<const u32x4*>(L + (int64_t)(b * 16 + m) * c + kc);
-            } else {
-                // L[k0 .. k0+32) x r arrives as 16-byte vectors along r; kept in lb[u][*] until it is transposed
-                constexpr int VEC = 32 * r / 8;
-#pragma unroll
-                for (int b = 0; b < R16; ++b) {   // VEC = 64 * R16: one vector per lane per b
-                    int v = b * 64 + lane;
-                    int kk = v / (r / 8), p0 = (v % (r / 8)) * 8;
-                    const int km = k0 + (kk >> 3) * 16 + (kk & 7);   // slot kk of the step holds this column
-                    const int kr = km < c ? km : c - 1;
-                    lb[u][b] = *reinterpret_cast<const u32x4*>(L + (int64_t)kr * r + p0);
-                }
-                (void)VEC;
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < kLoraUnroll; ++u) {
-            if (!L_RC) {
-                // transpose this step's slice through the wavefront's LDS piece: lt[p][kk]
-#pragma unroll
-                for (int b = 0; b < R16; ++b) {
-                    int v = b * 64 + lane;
-                    int kk = v / (r / 8), p0 = (v % (r / 8)) * 8;
-#pragma unroll
-                    for (int w = 0; w < 4; ++w) {
-                        lt[wave][p0 + 2 * w][kk] = (uint16_t)(lb[u][b][w] & 0xFFFFu);
-                        lt[wave][p0 + 2 * w + 1][kk] = (uint16_t)(lb[u][b][w] >> 16);
-                    }
-                }
-#pragma unroll
-                for (int b = 0; b < R16; ++b)
-                    lb[u][b] = *reinterpret_cast<const u32x4*>(&lt[wave][b * 16 + m][g * 8]);
-            }
-#pragma unroll
-            for (int b = 0; b < R16; ++b)
-                acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xa[u]),
-                                                                 __builtin_bit_cast(bf16x8, lb[u][b]), acc[b], 0, 0, 0);
-        }
-    }
-#pragma unroll
-    for (int b = 0; b < R16; ++b)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) red[wave][b][lane][v] = acc[b][v];
-    __syncthreads();
-    // fixed-order sum over the wavefronts; element v of lane (m, g) is T[row0 + 4 g + v][16 b + m]
-    for (int e = threadIdx.x; e < R16 * 64 * 4; e += NT) {
-        int v = e & 3, ln = (e >> 2) & 63, b = e >> 8;
-        float s = 0.0f;
-#pragma unroll
-        for (int w = 0; w < kLoraWaves; ++w) s += red[w][b][ln][v];
-        s = s * scale;
-        int64_t orow = (int64_t)blockIdx.x * 16 + (ln >> 4) * 4 + v;
-        if (orow < t) {
-            uint32_t hi = f32_to_bf16_rne(s);
-            float rest = s - __uint_as_float(hi << 16);
-            T_hi[orow * r + b * 16 + (ln & 15)] = (uint16_t)hi;
-            T_lo[orow * r + b * 16 + (ln & 15)] = (uint16_t)f32_to_bf16_rne(rest);
-        }
-    }
+    lora_down_body<R16, L_RC>(blockIdx.x, blockIdx.y, gridDim.x, X, t, c, ldx, L, scale, T_hi, T_lo, row_blocks, tr_src,
+                              tr_dst, tr_rows, tr_cols);
 }
 
 template <bool L_RC>

@@ -1,0 +1,139 @@
+// Device code of the fused column scaling and per-token INT8 quantization (Eq. 5 then Eq. 1 of the paper), shared by
+// the stand-alone quantizer launch and by the launch that runs it next to the LoRA down-projection.
+#pragma once
+#include "quaff_internal.h"
+
+namespace quaff {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// scaled fp32 values of eight consecutive bf16 elements
+__device__ __forceinline__ void widen_scale(const u32x4& raw, const float* __restrict__ cs, int64_t col, float (&v)[8]) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        v[2 * u] = __uint_as_float(raw[u] << 16);
+        v[2 * u + 1] = __uint_as_float(raw[u] & 0xFFFF0000u);
+    }
+    if (cs) {
+        f32x4 c0 = *reinterpret_cast<const f32x4*>(cs + col);
+        f32x4 c1 = *reinterpret_cast<const f32x4*>(cs + col + 4);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            v[u] = __fmul_rn(v[u], c0[u]);
+            v[4 + u] = __fmul_rn(v[4 + u], c1[u]);
+        }
+    }
+}
+
+__device__ __forceinline__ u32x2 pack_codes(const float (&v)[8], float c) {
+    u32x2 out;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) w |= (uint32_t)(rtn_code(v[4 * h + u], c) & 0xFF) << (8 * u);
+        out[h] = w;
+    }
+    return out;
+}
+
+// compact copy of the outlier columns' codes: xq_O[row, k] = code(X[row, O_k]), zero beyond n
+__device__ __forceinline__ void write_outlier_codes(const uint16_t* __restrict__ xrow, const float* __restrict__ cs,
+                                                    const int32_t* __restrict__ O, int n, int n_pad, float c,
+                                                    int8_t* __restrict__ dst, int lane, int nlanes) {
+    for (int k = lane; k < n_pad; k += nlanes) {
+        int q = 0;
+        if (k < n) {
+            int col = O[k];
+            float x = bf16_bits_to_f32(xrow[col]);
+            if (cs) x = __fmul_rn(x, cs[col]);
+            q = rtn_code(x, c);
+        }
+        dst[k] = (int8_t)q;
+    }
+}
+
+// Work of one workgroup of NT threads whose index among the quantizing workgroups is `block`.
+// TPR threads cooperate on one row (64 = a wavefront, 256 = four wavefronts); each holds NV vectors of 8 elements.
+template <int NT, int TPR, int NV>
+__device__ __forceinline__ void quant_rows_body(int block, const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx,
+                                                const float* __restrict__ cs, const int32_t* __restrict__ O, int n,
+                                                int n_pad, int8_t* __restrict__ Xq, float* __restrict__ delta,
+                                                int8_t* __restrict__ xq_O) {
+    constexpr int RPB = NT / TPR;   // rows per workgroup
+    __shared__ float red[NT / 64];
+    const int lane = threadIdx.x % TPR;
+    const int64_t row = (int64_t)block * RPB + threadIdx.x / TPR;
+    const bool live = row < t;
+    const uint16_t* xrow = X + (live ? row : 0) * ldx;
+
+    u32x4 raw[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        int col = (i * TPR + lane) * 8;
+        raw[i] = (u32x4){0, 0, 0, 0};
+        if (live && col < c) raw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xrow + col));
+    }
+    // the outlier columns' values are gathered now so that their (dependent) loads overlap the row loads
+    constexpr int GPL = 4;                       // gathered outliers per lane in registers (TPR * GPL per row)
+    float xo[GPL];
+    const bool gather_regs = xq_O && n_pad <= TPR * GPL;
+    if (gather_regs) {
+#pragma unroll
+        for (int u = 0; u < GPL; ++u) {
+            int k = lane + u * TPR;
+            xo[u] = 0.0f;
+            if (live && k < n) {
+                int col = O[k];
+                float x = bf16_bits_to_f32(xrow[col]);
+                xo[u] = cs ? __fmul_rn(x, cs[col]) : x;
+            }
+        }
+    }
+    float m = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        int col = (i * TPR + lane) * 8;
+        if (col < c) {
+            float v[8];
+            widen_scale(raw[i], cs, col, v);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) m = fmaxf(m, fabsf(v[u]));
+        }
+    }
+    m = wave_max(m);
+    if (TPR == 256) {
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+        __syncthreads();
+        const int w0 = (threadIdx.x / TPR) * 4;   // the four wavefronts of this row
+        m = fmaxf(fmaxf(red[w0], red[w0 + 1]), fmaxf(red[w0 + 2], red[w0 + 3]));
+    }
+    if (!live) return;
+    float d, cc;
+    rtn_steps(m, d, cc);
+    if (lane == 0) delta[row] = d;
+    int8_t* qrow = Xq + row * (int64_t)c;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        int col = (i * TPR + lane) * 8;
+        if (col < c) {
+            float v[8];
+            widen_scale(raw[i], cs, col, v);
+            *reinterpret_cast<u32x2*>(qrow + col) = pack_codes(v, cc);
+        }
+    }
+    if (gather_regs) {
+        int8_t* dst = xq_O + row * (int64_t)n_pad;
+#pragma unroll
+        for (int u = 0; u < GPL; ++u) {
+            int k = lane + u * TPR;
+            if (k < n_pad) dst[k] = (int8_t)rtn_code(xo[u], cc);   // xo = 0 beyond n: code 0
+        }
+    } else if (xq_O) {
+        write_outlier_codes(xrow, cs, O, n, n_pad, cc, xq_O + row * (int64_t)n_pad, lane, TPR);
+    }
+}
+
+}  // namespace quaff
