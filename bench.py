@@ -28,6 +28,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload (BASELINE.json configs, 1-based)")
     ap.add_argument("--batches", type=int, default=4, help="distinct input batches rotated through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="forward as scale_update + quant_act + linear_fwd instead of the one-call forward step")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this path is built and measured on ONE GPU only (no collectives, no sharding); "
@@ -76,7 +78,8 @@ def main():
         L["cs"] = torch.ones(p.c_in, dtype=f32, device=dev)
         L["what"] = torch.zeros((p.c_out, max(n_pad, 1)), dtype=i8, device=dev)
         L["dwh"] = torch.zeros(p.c_out, dtype=f32, device=dev)
-        L["ws"] = torch.empty(q.workspace_bytes(p.t, p.c_in, p.c_out, n, r), dtype=i8, device=dev)
+        L["ws"] = torch.empty(max(q.workspace_bytes(p.t, p.c_in, p.c_out, n, r),
+                                  q.fwd_step_workspace_bytes(p.t, p.c_in, p.c_out, n, r)), dtype=i8, device=dev)
         L["X"] = [bf16_dev(synth.activations(p, s)) for s in range(args.batches)]
         L["dY"] = [bf16_dev(synth.out_grad(p, s)) for s in range(args.batches)] if p.backward else None
         L["Xq"] = torch.empty((p.t, p.c_in), dtype=i8, device=dev)
@@ -93,12 +96,17 @@ def main():
         for L in layers:
             p, n, r = L["p"], L["n"], L["r"]
             X = L["X"][b]
-            q.scale_update(X, L["O"], L["W_O"], L["wmax"], p.c_out, p.gamma, L["s"], L["cs"], L["what"], L["dwh"],
-                           None, L["ws"])
-            q.quant_act(X, L["cs"], L["O"], L["Xq"], L["dx"], L["xo"] if n else None)
-            q.linear_fwd(L["Xq"], L["dx"], L["xo"] if n else None, L["Wq"], L["dw"], p.c_in, p.c_out,
-                         L["what"] if n else None, L["dwh"] if n else None, n, X if r else None, L["A"], L["B"], r,
-                         p.lora_scale, L["Y"][b], L["ws"])
+            if args.separate_calls:
+                q.scale_update(X, L["O"], L["W_O"], L["wmax"], p.c_out, p.gamma, L["s"], L["cs"], L["what"], L["dwh"],
+                               None, L["ws"])
+                q.quant_act(X, L["cs"], L["O"], L["Xq"], L["dx"], L["xo"] if n else None)
+                q.linear_fwd(L["Xq"], L["dx"], L["xo"] if n else None, L["Wq"], L["dw"], p.c_in, p.c_out,
+                             L["what"] if n else None, L["dwh"] if n else None, n, X if r else None, L["A"], L["B"], r,
+                             p.lora_scale, L["Y"][b], L["ws"])
+            else:
+                q.linear_fwd_step(X, L["O"], L["W_O"] if n else None, L["wmax"] if n else None, p.c_out, p.gamma,
+                                  L["s"], L["cs"], L["what"], L["dwh"], None, L["Xq"], L["dx"], L["xo"] if n else None,
+                                  L["Wq"], L["dw"], L["A"], L["B"], r, p.lora_scale, L["Y"][b], L["ws"])
             if p.backward:
                 q.linear_bwd_dx(L["dY"][b], L["Wq"], L["dw"], p.c_in, p.c_out, L["A"], L["B"], r, p.lora_scale,
                                 L["dX"][b], L["ws"])
@@ -199,12 +207,15 @@ def main():
         hbm("quant_rows", quant_bytes)
         hbm("quant_rows+lora_down", fused_bytes)
         hbm("lora_down", lora_bytes)
+        hbm("colmax_outlier+lora_down", lora_bytes)   # the abs-max gather adds about a third of X's bytes
     else:   # rank 0 or shapes the combined launch does not cover: separate launches in the backward pass too
         hbm("quant_rows", quant_bytes + fused_bytes)
         hbm("lora_down", lora_bytes)
     # column abs-max: useful bytes are the 2-byte outlier entries; what the memory system must fetch is one
     # 64-byte segment per (row, distinct segment touched by O) - counted here from the outlier positions
-    if "colmax_outlier" in kernels:
+    for col_kind in ("colmax_outlier",):
+        if col_kind not in kernels:
+            continue
         useful = fetched = 0.0
         for L in layers:
             if L["n"]:
@@ -237,7 +248,8 @@ def main():
         "config": {"workload": "configs[%d]: %s" % (args.config - 1, ", ".join(
             "%s t=%d %d->%d |O|=%d r=%d" % (L["p"].name, L["p"].t, L["p"].c_in, L["p"].c_out, L["n"], L["r"])
             for L in layers)), "batches_rotated": args.batches, "calls_per_step":
-            "scale_update, quant_act, linear_fwd, linear_bwd_dx per projection"},
+            ("scale_update, quant_act, linear_fwd, linear_bwd_dx per projection" if args.separate_calls else
+             "linear_fwd_step (= scale_update + quant_act + linear_fwd), linear_bwd_dx per projection")},
         "frac_int8_peak_whole_step": round(tops / INT8_PEAK_TOPS, 4),
         "wall_ms_per_step": round(wall_ms / args.steps, 5),
         "warm_same_batch_ms_per_step": round(warm_ms_per_step, 5),

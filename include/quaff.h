@@ -136,6 +136,22 @@ int quaff_linear_fwd(const int8_t* Xq, const float* delta_x, const int8_t* xq_O,
                      const uint16_t* lora_A, const uint16_t* lora_B, int32_t lora_rank, float lora_scale, float* Y,
                      int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * One call for the whole forward step of a layer: quaff_scale_update, quaff_quant_act and quaff_linear_fwd with the
+ * same arguments, the same results bit for bit and the same side effects (s_O, colscale, what_int, delta_what,
+ * cmax_out, Xq, delta_x, xq_O are all written as by the three calls).  Knowing the whole step lets the library
+ * run kernels that do not depend on each other in one launch (the outlier-column abs-max next to the LoRA
+ * down-projection, both of which only read X); cases that gain nothing run the three calls one after the other.
+ * `workspace` must hold quaff_fwd_step_workspace_bytes(t, c_in, c_out, n_outlier, lora_rank) bytes.
+ */
+size_t quaff_fwd_step_workspace_bytes(int64_t t, int64_t c_in, int64_t c_out, int32_t n_outlier, int32_t lora_rank);
+int quaff_linear_fwd_step(const uint16_t* X, int64_t t, int64_t c_in, int64_t ldx, const int32_t* O, int32_t n_outlier,
+                          const float* W_O, const float* wmax_O, int64_t c_out, float gamma, float* s_O,
+                          float* colscale, int8_t* what_int, float* delta_what, float* cmax_out, int8_t* Xq,
+                          float* delta_x, int8_t* xq_O, const void* Wq_packed, const float* delta_w,
+                          const uint16_t* lora_A, const uint16_t* lora_B, int32_t lora_rank, float lora_scale, float* Y,
+                          int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Same product as quaff_linear_fwd, but the exact int32 accumulators of Eq. 9 are written instead of Y
  * (acc1, acc2: [t x c_out] int32, dense; acc2 may be NULL).  For checking the integer path bit for bit. */
 int quaff_linear_fwd_acc(const int8_t* Xq, const int8_t* xq_O, int64_t t, const void* Wq_packed, int64_t c_in,

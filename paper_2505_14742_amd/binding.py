@@ -42,6 +42,9 @@ SIGNATURES = {
     "quaff_calibrate_workspace_bytes": (_sz, [_i64, _i32]),
     "quaff_calibrate_outliers": (C.c_int, [_vp, _i64, _i64, _i64, _vp, _i32, C.c_double, _i32, _vp, _vp, _vp, _vp, _sz,
                                            _vp]),
+    "quaff_fwd_step_workspace_bytes": (_sz, [_i64, _i64, _i64, _i32, _i32]),
+    "quaff_linear_fwd_step": (C.c_int, [_vp, _i64, _i64, _i64, _vp, _i32, _vp, _vp, _i64, _f32, _vp, _vp, _vp, _vp, _vp,
+                                        _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _f32, _vp, _i64, _vp, _sz, _vp]),
     "quaff_profile_enable": (C.c_int, [C.c_int]),
     "quaff_profile_collect": (_i64, []),
     "quaff_profile_launch": (C.c_int, [_i64, C.POINTER(C.c_int), C.POINTER(C.c_float)]),
@@ -195,6 +198,23 @@ def calibrate_outliers(X, sample_offsets, ratio, budget, xi, O, n_outlier, works
                                           _ptr(n_outlier), _ptr(workspace),
                                           0 if workspace is None else workspace.numel() * workspace.element_size(),
                                           _stream()))
+
+
+def fwd_step_workspace_bytes(t, c_in, c_out, n_outlier, lora_rank) -> int:
+    return int(lib().quaff_fwd_step_workspace_bytes(t, c_in, c_out, n_outlier, lora_rank))
+
+
+def linear_fwd_step(X, O, W_O, wmax_O, c_out, gamma, s_O, colscale, what_int, delta_what, cmax_out, Xq, delta_x, xq_O,
+                    Wq_packed, delta_w, lora_A, lora_B, lora_rank, lora_scale, Y, workspace):
+    t, c_in = X.shape[0], X.shape[1]
+    n = 0 if O is None else O.numel()
+    _check(lib().quaff_linear_fwd_step(_ptr(X), t, c_in, X.stride(0), _ptr(O), n, _ptr(W_O), _ptr(wmax_O), c_out,
+                                       float(gamma), _ptr(s_O), _ptr(colscale), _ptr(what_int), _ptr(delta_what),
+                                       _ptr(cmax_out), _ptr(Xq), _ptr(delta_x), _ptr(xq_O), _ptr(Wq_packed),
+                                       _ptr(delta_w), _ptr(lora_A), _ptr(lora_B), lora_rank, float(lora_scale),
+                                       _ptr(Y), Y.stride(0), _ptr(workspace),
+                                       0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                       _stream()))
 
 
 def linear_bwd_dx_acc(dY, Wq_packed, delta_w, c_in, c_out, Gq, delta_g, acc):

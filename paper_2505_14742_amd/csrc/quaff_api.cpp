@@ -373,4 +373,71 @@ int quaff_calibrate_outliers(const uint16_t* X, int64_t t_total, int64_t c_in, i
                                               static_cast<hipStream_t>(stream)));
 }
 
+size_t quaff_fwd_step_workspace_bytes(int64_t t, int64_t c_in, int64_t c_out, int32_t n_outlier, int32_t lora_rank) {
+    if (t <= 0 || c_in <= 0 || c_out <= 0 || n_outlier < 0 || lora_rank < 0) return 0;
+    return ws_scale(t, n_outlier) + ws_fwd(t, c_out, lora_rank).total + 256;
+}
+
+int quaff_linear_fwd_step(const uint16_t* X, int64_t t, int64_t c_in, int64_t ldx, const int32_t* O, int32_t n_outlier,
+                          const float* W_O, const float* wmax_O, int64_t c_out, float gamma, float* s_O,
+                          float* colscale, int8_t* what_int, float* delta_what, float* cmax_out, int8_t* Xq,
+                          float* delta_x, int8_t* xq_O, const void* Wq_packed, const float* delta_w,
+                          const uint16_t* lora_A, const uint16_t* lora_B, int32_t lora_rank, float lora_scale, float* Y,
+                          int64_t ldy, void* workspace, size_t workspace_bytes, void* stream) {
+    if (t <= 0 || c_in <= 0 || c_out <= 0 || n_outlier < 0 || !rank_ok(lora_rank)) return QUAFF_ERR_SHAPE;
+    const size_t scale_bytes = ws_scale(t, n_outlier);
+    if (!workspace || workspace_bytes < scale_bytes + ws_fwd(t, c_out, lora_rank).total) return QUAFF_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return QUAFF_ERR_ALIGN;
+    if (!colscale) return QUAFF_ERR_NULL;
+    if (n_outlier > 0 && !xq_O) return QUAFF_ERR_NULL;
+    char* base = static_cast<char*>(workspace);
+    void* ws_lin = base + scale_bytes;
+    const size_t ws_lin_bytes = workspace_bytes - scale_bytes;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // the combined first launch covers the usual case; everything else is the three calls one after the other
+    const bool combined = n_outlier > 0 && n_outlier <= 1024 && (int64_t)n_outlier * 64 < c_in && lora_rank > 0;
+    if (!combined) {
+        int st = quaff_scale_update(X, t, c_in, ldx, O, n_outlier, W_O, wmax_O, c_out, gamma, s_O, colscale, what_int,
+                                    delta_what, cmax_out, workspace, scale_bytes, stream);
+        if (st != QUAFF_OK) return st;
+        st = quaff_quant_act(X, t, c_in, ldx, colscale, O, n_outlier, Xq, delta_x, xq_O, stream);
+        if (st != QUAFF_OK) return st;
+        return quaff_linear_fwd(Xq, delta_x, xq_O, t, Wq_packed, delta_w, c_in, c_out, what_int, delta_what,
+                                n_outlier, X, ldx, lora_A, lora_B, lora_rank, lora_scale, Y, ldy, ws_lin, ws_lin_bytes,
+                                stream);
+    }
+    // argument checks of the three calls (same conditions, same codes)
+    if (!X || !O || !W_O || !wmax_O || !s_O || !what_int || !delta_what || !Xq || !delta_x || !Wq_packed || !delta_w ||
+        !lora_A || !lora_B || !Y)
+        return QUAFF_ERR_NULL;
+    if (!dims_ok(t, c_in, c_out) || n_outlier > c_in || ldx < c_in || ldy < c_out || !(gamma >= 0.0f && gamma <= 1.0f))
+        return QUAFF_ERR_SHAPE;
+    if (!aligned16(X) || !aligned16(what_int) || !aligned16(Xq) || !aligned16(colscale) || !aligned16(xq_O) ||
+        !aligned16(Wq_packed) || !aligned16(lora_A) || !aligned16(lora_B) || ldx % 8 != 0)
+        return QUAFF_ERR_ALIGN;
+    float* wsf = static_cast<float*>(workspace);
+    const int nslab = quaff::scale_update_gather_slabs(t, n_outlier);
+    uint32_t* part = reinterpret_cast<uint32_t*>(wsf);
+    float* s_prev = wsf + (int64_t)nslab * n_outlier;
+    FwdWs w = ws_fwd(t, c_out, lora_rank);
+    char* lin = static_cast<char*>(ws_lin);
+    uint16_t* t_hi = reinterpret_cast<uint16_t*>(lin + w.t_hi);
+    uint16_t* t_lo = reinterpret_cast<uint16_t*>(lin + w.t_lo);
+    uint16_t* lt = reinterpret_cast<uint16_t*>(lin + w.lt);
+    int st = hip_status(quaff::launch_colmax_lora(X, t, c_in, ldx, O, n_outlier, part, s_O, s_prev, nslab, lora_A,
+                                                  lora_rank, lora_scale, t_hi, t_lo, lora_B, lt, c_out, s));
+    if (st != QUAFF_OK) return st;
+    st = hip_status(quaff::launch_momentum(part, nslab, n_outlier, pad_outliers(n_outlier), wmax_O, s_prev, gamma, O,
+                                           s_O, colscale, cmax_out, W_O, c_out, what_int, delta_what, s));
+    if (st != QUAFF_OK) return st;
+    st = hip_status(quaff::launch_quant_act(X, t, c_in, ldx, colscale, O, n_outlier, Xq, delta_x, xq_O, s));
+    if (st != QUAFF_OK) return st;
+    quaff::GemmArgs g;
+    st = fwd_common(Xq, delta_x, xq_O, t, Wq_packed, delta_w, c_in, c_out, what_int, delta_what, n_outlier, g);
+    if (st != QUAFF_OK) return st;
+    g.T_hi = t_hi; g.T_lo = t_lo; g.L = lt; g.r = lora_rank;
+    g.C = Y; g.ldc = ldy;
+    return hip_status(quaff::launch_gemm(g, false, s));
+}
+
 }  // extern "C"

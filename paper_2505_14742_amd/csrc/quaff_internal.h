@@ -39,7 +39,7 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 // ---- optional per-launch timing (see quaff_profile_* in the C ABI) ------------------------------------
-enum KernelKind { K_PREPARE = 0, K_COLMAX, K_MOMENTUM, K_QUANT, K_LORA, K_GEMM, K_LORA_GRAD, K_OUTLIER_GRAD, K_CALIB, K_QUANT_LORA, KERNEL_KINDS };
+enum KernelKind { K_PREPARE = 0, K_COLMAX, K_MOMENTUM, K_QUANT, K_LORA, K_GEMM, K_LORA_GRAD, K_OUTLIER_GRAD, K_CALIB, K_QUANT_LORA, K_COLMAX_LORA, KERNEL_KINDS };
 class ProfScope {
 public:
     ProfScope(int kind, hipStream_t stream);
@@ -99,6 +99,17 @@ hipError_t launch_calibrate(const uint16_t* X, int64_t ldx, int64_t c_in, int64_
 bool launch_quant_lora(const uint16_t* X, int64_t t, int64_t c, int64_t ldx, const float* cs, int8_t* Xq, float* delta,
                        const uint16_t* L_r_by_c, int32_t r, float scale, uint16_t* T_hi, uint16_t* T_lo,
                        hipStream_t stream, hipError_t* err);
+
+// Pieces of the fused forward step (quaff_linear_fwd_step): the abs-max slabs and the LoRA down-projection of X in
+// one launch (quaff_fwd_step.hip), then the momentum / what kernel on those slabs (quaff_scale.hip).
+int scale_update_gather_slabs(int64_t t, int32_t n);   // slab count the gather variant of the abs-max uses
+hipError_t launch_colmax_lora(const uint16_t* X, int64_t t, int64_t c, int64_t ldx, const int32_t* O, int32_t n,
+                              uint32_t* part, const float* s_O, float* s_prev, int nslab, const uint16_t* A, int32_t r,
+                              float scale, uint16_t* T_hi, uint16_t* T_lo, const uint16_t* B, uint16_t* Bt,
+                              int64_t c_out, hipStream_t stream);
+hipError_t launch_momentum(const uint32_t* part, int nslab, int n, int n_pad, const float* wmax_O, const float* s_prev,
+                           float gamma, const int32_t* O, float* s_O, float* colscale, float* cmax_out,
+                           const float* W_O, int64_t c_out, int8_t* what_int, float* delta_what, hipStream_t stream);
 
 struct GemmArgs {
     // C[M x N] from A [M x K] int8 (lda) and B [N x K] int8 (ldb), both contraction-contiguous

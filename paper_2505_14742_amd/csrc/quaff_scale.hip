@@ -10,12 +10,10 @@
 //                           1/s and cmax; then each thread requantizes one output channel of what.
 // Maxima of non-negative floats are taken on their bit patterns (same order as unsigned integers) with LDS
 // atomics, which is exact and independent of the order of arrival.
-#include "quaff_internal.h"
+#include "quaff_scale_body.h"
 
 namespace quaff {
 
-constexpr int kRowsPerSlab = 16;
-constexpr int kMaxSlabs = 128;
 constexpr int kWhatThreads = 128;   // output channels per workgroup of momentum_what_kernel
 constexpr int kPartBatch = 32;     // partial maxima loaded per thread before the first is used
 
@@ -24,37 +22,11 @@ int scale_update_blocks(int64_t t) {
     return (int)(b < kMaxSlabs ? b : kMaxSlabs);
 }
 
-// part[slab][k] = max over the slab's rows of |X[row, O_k]|; slab s owns row groups s, s + nslab, ...
 __global__ void __launch_bounds__(256)
 colmax_outlier_kernel(const uint16_t* __restrict__ X, int64_t t, int64_t ldx, const int32_t* __restrict__ O, int n,
                       uint32_t* __restrict__ part, const float* __restrict__ s_O, float* __restrict__ s_prev) {
     extern __shared__ uint32_t smax[];   // [n]
-    const int nslab = gridDim.x;
-    for (int k = threadIdx.x; k < n; k += 256) smax[k] = 0u;
-    if (blockIdx.x == 0)
-        for (int k = threadIdx.x; k < n; k += 256) s_prev[k] = s_O[k];
-    __syncthreads();
-    const int per_group = kRowsPerSlab * n;
-    for (int64_t r0 = (int64_t)blockIdx.x * kRowsPerSlab; r0 < t; r0 += (int64_t)nslab * kRowsPerSlab) {
-        for (int e0 = threadIdx.x; e0 < per_group; e0 += 4 * 256) {   // four independent gathers in flight per thread
-            uint32_t mag[4];
-            int kk[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                int e = e0 + u * 256;
-                int ec = e < per_group ? e : per_group - 1;
-                int r = ec / n;
-                kk[u] = ec - r * n;
-                int64_t row = r0 + r < t ? r0 + r : t - 1;
-                mag[u] = ((uint32_t)X[row * ldx + O[kk[u]]] & 0x7FFFu) << 16;   // |x| as fp32 bits
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-                if (e0 + u * 256 < per_group) atomicMax(&smax[kk[u]], mag[u]);
-        }
-    }
-    __syncthreads();
-    for (int k = threadIdx.x; k < n; k += 256) part[(int64_t)blockIdx.x * n + k] = smax[k];
+    colmax_outlier_body<256>(blockIdx.x, gridDim.x, smax, X, t, ldx, O, n, part, s_O, s_prev);
 }
 
 __global__ void __launch_bounds__(kWhatThreads)
@@ -293,10 +265,13 @@ momentum_what_wide_kernel(const uint32_t* __restrict__ part, int nslab, int n, i
     }
 }
 
-static hipError_t launch_momentum(const uint32_t* part, int nslab, int n, int n_pad, const float* wmax_O,
-                                  const float* s_prev, float gamma, const int32_t* O, float* s_O, float* colscale,
-                                  float* cmax_out, const float* W_O, int64_t c_out, int8_t* what_int,
-                                  float* delta_what, hipStream_t stream);
+// as many slabs as the rows allow, but no more partial maxima than momentum_what_kernel reduces in one batch
+int scale_update_gather_slabs(int64_t t, int32_t n) {
+    int nslab = scale_update_blocks(t);
+    const int one_batch = kPartBatch * kWhatThreads / n;
+    const int cap = one_batch > 16 ? one_batch : 16;
+    return nslab < cap ? nslab : cap;
+}
 
 hipError_t launch_scale_update(const uint16_t* X, int64_t t, int64_t c_in, int64_t ldx, const int32_t* O, int32_t n,
                                const float* W_O, const float* wmax_O, int64_t c_out, float gamma, float* s_O,
@@ -322,9 +297,7 @@ hipError_t launch_scale_update(const uint16_t* X, int64_t t, int64_t c_in, int64
         return launch_momentum(part, nslab, n, n_pad, wmax_O, s_prev, gamma, O, s_O, colscale, cmax_out, W_O, c_out,
                                what_int, delta_what, stream);
     }
-    // as many slabs as the rows allow, but no more partial maxima than momentum_what_kernel reduces in one batch
-    const int one_batch = kPartBatch * kWhatThreads / n;
-    if (nslab > one_batch) nslab = one_batch > 16 ? one_batch : 16;
+    nslab = scale_update_gather_slabs(t, n);
     float* s_prev = ws + (int64_t)nslab * n;            // [n]
     {
         ProfScope prof(K_COLMAX, stream);
@@ -335,7 +308,7 @@ hipError_t launch_scale_update(const uint16_t* X, int64_t t, int64_t c_in, int64
                            what_int, delta_what, stream);
 }
 
-static hipError_t launch_momentum(const uint32_t* part, int nslab, int n, int n_pad, const float* wmax_O,
+hipError_t launch_momentum(const uint32_t* part, int nslab, int n, int n_pad, const float* wmax_O,
                                   const float* s_prev, float gamma, const int32_t* O, float* s_O, float* colscale,
                                   float* cmax_out, const float* W_O, int64_t c_out, int8_t* what_int,
                                   float* delta_what, hipStream_t stream) {

@@ -96,6 +96,17 @@ class Layer:
                      self.c_out, self.what_int if self.n else None, self.delta_what if self.n else None, self.n,
                      X if self.r else None, self.A, self.B, self.r, self.lora_scale, self.Y, self.ws)
 
+    def fwd_step(self, X, gamma):
+        """The three forward calls as one (quaff_linear_fwd_step), on a workspace of its own."""
+        if not hasattr(self, "ws_step") or self.ws_step_t != self.t:
+            self.ws_step = torch.empty(q.fwd_step_workspace_bytes(self.t, self.c_in, self.c_out, self.n, self.r),
+                                       dtype=torch.int8, device=DEV)
+            self.ws_step_t = self.t
+        q.linear_fwd_step(X, self.O, self.W_O if self.n else None, self.wmax_O if self.n else None, self.c_out, gamma,
+                          self.s_O, self.colscale, self.what_int, self.delta_what, self.cmax, self.Xq, self.delta_x,
+                          self.xq_O if self.n else None, self.Wq_packed, self.delta_w, self.A, self.B, self.r,
+                          self.lora_scale, self.Y, self.ws_step)
+
     def linear_fwd_acc(self):
         acc1 = torch.empty((self.t, self.c_out), dtype=torch.int32, device=DEV)
         acc2 = torch.empty((self.t, self.c_out), dtype=torch.int32, device=DEV)
