@@ -39,7 +39,7 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 // ---- optional per-launch timing (see quaff_profile_* in the C ABI) ------------------------------------
-enum KernelKind { K_PREPARE = 0, K_COLMAX, K_MOMENTUM, K_QUANT, K_LORA, K_GEMM, K_LORA_GRAD, K_OUTLIER_GRAD, K_CALIB, K_QUANT_LORA, K_COLMAX_LORA, KERNEL_KINDS };
+enum KernelKind { K_PREPARE = 0, K_COLMAX, K_MOMENTUM, K_QUANT, K_LORA, K_GEMM, K_LORA_GRAD, K_OUTLIER_GRAD, K_CALIB, K_QUANT_LORA, K_COLMAX_LORA, K_WHAT_QUANT, KERNEL_KINDS };
 class ProfScope {
 public:
     ProfScope(int kind, hipStream_t stream);
@@ -110,6 +110,13 @@ hipError_t launch_colmax_lora(const uint16_t* X, int64_t t, int64_t c, int64_t l
 hipError_t launch_momentum(const uint32_t* part, int nslab, int n, int n_pad, const float* wmax_O, const float* s_prev,
                            float gamma, const int32_t* O, float* s_O, float* colscale, float* cmax_out,
                            const float* W_O, int64_t c_out, int8_t* what_int, float* delta_what, hipStream_t stream);
+
+// Momentum / what requantization and the quantizer of X in ONE launch (quaff_what_quant.hip); arguments as for
+// launch_momentum and launch_quant_act.  Returns false, with nothing enqueued, for shapes it does not cover.
+bool launch_what_quant(const uint32_t* part, int nslab, int32_t n, const float* wmax_O, const float* s_prev, float gamma,
+                       const int32_t* O, float* s_O, float* colscale, float* cmax_out, const float* W_O, int64_t c_out,
+                       int8_t* what_int, float* delta_what, const uint16_t* X, int64_t t, int64_t c, int64_t ldx,
+                       int8_t* Xq, float* delta, int8_t* xq_O, hipStream_t stream, hipError_t* err);
 
 struct GemmArgs {
     // C[M x N] from A [M x K] int8 (lda) and B [N x K] int8 (ldb), both contraction-contiguous

@@ -9,16 +9,28 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// The column scales may live in global memory (const float*) or in LDS (const lds_float*).
+typedef __attribute__((address_space(3))) float lds_float;
+template <class P> struct Vec4Of;
+template <> struct Vec4Of<const float*> { typedef const f32x4* type; };
+template <> struct Vec4Of<const lds_float*> { typedef const __attribute__((address_space(3))) f32x4* type; };
+struct NoPrologue { __device__ __forceinline__ void operator()() const {} };
+// "are there column scales at all": a global pointer may be null; an LDS copy always exists (and may legitimately
+// sit at LDS offset 0, which must not be mistaken for a null pointer)
+__device__ __forceinline__ bool has_scales(const float* cs) { return cs != nullptr; }
+__device__ __forceinline__ bool has_scales(const lds_float*) { return true; }
+
 // scaled fp32 values of eight consecutive bf16 elements
-__device__ __forceinline__ void widen_scale(const u32x4& raw, const float* __restrict__ cs, int64_t col, float (&v)[8]) {
+template <class CsPtr>
+__device__ __forceinline__ void widen_scale(const u32x4& raw, CsPtr cs, int64_t col, float (&v)[8]) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         v[2 * u] = __uint_as_float(raw[u] << 16);
         v[2 * u + 1] = __uint_as_float(raw[u] & 0xFFFF0000u);
     }
-    if (cs) {
-        f32x4 c0 = *reinterpret_cast<const f32x4*>(cs + col);
-        f32x4 c1 = *reinterpret_cast<const f32x4*>(cs + col + 4);
+    if (has_scales(cs)) {
+        f32x4 c0 = *(typename Vec4Of<CsPtr>::type)(cs + col);
+        f32x4 c1 = *(typename Vec4Of<CsPtr>::type)(cs + col + 4);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             v[u] = __fmul_rn(v[u], c0[u]);
@@ -40,7 +52,8 @@ __device__ __forceinline__ u32x2 pack_codes(const float (&v)[8], float c) {
 }
 
 // compact copy of the outlier columns' codes: xq_O[row, k] = code(X[row, O_k]), zero beyond n
-__device__ __forceinline__ void write_outlier_codes(const uint16_t* __restrict__ xrow, const float* __restrict__ cs,
+template <class CsPtr>
+__device__ __forceinline__ void write_outlier_codes(const uint16_t* __restrict__ xrow, CsPtr cs,
                                                     const int32_t* __restrict__ O, int n, int n_pad, float c,
                                                     int8_t* __restrict__ dst, int lane, int nlanes) {
     for (int k = lane; k < n_pad; k += nlanes) {
@@ -48,7 +61,7 @@ __device__ __forceinline__ void write_outlier_codes(const uint16_t* __restrict__
         if (k < n) {
             int col = O[k];
             float x = bf16_bits_to_f32(xrow[col]);
-            if (cs) x = __fmul_rn(x, cs[col]);
+            if (has_scales(cs)) x = __fmul_rn(x, cs[col]);
             q = rtn_code(x, c);
         }
         dst[k] = (int8_t)q;
@@ -57,11 +70,13 @@ __device__ __forceinline__ void write_outlier_codes(const uint16_t* __restrict__
 
 // Work of one workgroup of NT threads whose index among the quantizing workgroups is `block`.
 // TPR threads cooperate on one row (64 = a wavefront, 256 = four wavefronts); each holds NV vectors of 8 elements.
-template <int NT, int TPR, int NV>
+// `prologue` runs (on every thread of the workgroup; it may contain barriers) after the row loads have been issued
+// and before the column scales are first read: the launch that derives the scales itself hides that work there.
+template <int NT, int TPR, int NV, class CsPtr = const float*, class Prologue = NoPrologue>
 __device__ __forceinline__ void quant_rows_body(int block, const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx,
-                                                const float* __restrict__ cs, const int32_t* __restrict__ O, int n,
-                                                int n_pad, int8_t* __restrict__ Xq, float* __restrict__ delta,
-                                                int8_t* __restrict__ xq_O) {
+                                                CsPtr cs, const int32_t* __restrict__ O, int n, int n_pad,
+                                                int8_t* __restrict__ Xq, float* __restrict__ delta,
+                                                int8_t* __restrict__ xq_O, Prologue prologue = Prologue()) {
     constexpr int RPB = NT / TPR;   // rows per workgroup
     __shared__ float red[NT / 64];
     const int lane = threadIdx.x % TPR;
@@ -76,6 +91,7 @@ __device__ __forceinline__ void quant_rows_body(int block, const uint16_t* __res
         raw[i] = (u32x4){0, 0, 0, 0};
         if (live && col < c) raw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xrow + col));
     }
+    prologue();
     // the outlier columns' values are gathered now so that their (dependent) loads overlap the row loads
     constexpr int GPL = 4;                       // gathered outliers per lane in registers (TPR * GPL per row)
     float xo[GPL];
@@ -88,7 +104,7 @@ __device__ __forceinline__ void quant_rows_body(int block, const uint16_t* __res
             if (live && k < n) {
                 int col = O[k];
                 float x = bf16_bits_to_f32(xrow[col]);
-                xo[u] = cs ? __fmul_rn(x, cs[col]) : x;
+                xo[u] = has_scales(cs) ? __fmul_rn(x, cs[col]) : x;
             }
         }
     }

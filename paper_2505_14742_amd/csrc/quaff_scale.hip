@@ -35,92 +35,9 @@ momentum_what_kernel(const uint32_t* __restrict__ part, int nslab, int n, int n_
                      float* __restrict__ s_O, float* __restrict__ colscale, float* __restrict__ cmax_out,
                      const float* __restrict__ W_O, int64_t c_out, int8_t* __restrict__ what_int,
                      float* __restrict__ delta_what) {
-    extern __shared__ float sm1[];                                  // [n] : s_k - 1
-    uint32_t* smax = reinterpret_cast<uint32_t*>(sm1 + n);         // [n]
-    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    const int64_t j = (int64_t)blockIdx.x * kWhatThreads + threadIdx.x;
-    const int64_t jc = j < c_out ? j : c_out - 1;
-    const bool small = n <= 64;
-    // Every global load that does not depend on the reduction is issued first, so that the kernel pays about one
-    // memory round trip instead of three: this thread's column of W_O (n <= 64: kept in registers), its share of the
-    // partial maxima, and the per-outlier constants.
-    float w[64];
-    if (small) {
-#pragma unroll
-        for (int k = 0; k < 64; ++k) w[k] = W_O[(int64_t)(k < n ? k : n - 1) * c_out + jc];
-    }
-    const int kk = threadIdx.x < n ? threadIdx.x : n - 1;          // outlier handled by this thread (first pass)
-    const float wmax0 = wmax_O[kk], sprev0 = s_prev[kk];
-    const int o0 = O[kk];
-    for (int k = threadIdx.x; k < n; k += kWhatThreads) smax[k] = 0u;
-    __syncthreads();
-    const int total = nslab * n;
-    for (int e0 = threadIdx.x; e0 < total; e0 += kPartBatch * kWhatThreads) {   // one round trip for up to 4096 partials
-        uint32_t v[kPartBatch];
-#pragma unroll
-        for (int u = 0; u < kPartBatch; ++u) {
-            int e = e0 + u * kWhatThreads;
-            v[u] = part[e < total ? e : total - 1];
-        }
-#pragma unroll
-        for (int u = 0; u < kPartBatch; ++u) {
-            int e = e0 + u * kWhatThreads;
-            if (e < total) atomicMax(&smax[e % n], v[u]);
-        }
-    }
-    __syncthreads();
-    for (int k = threadIdx.x; k < n; k += kWhatThreads) {
-        const bool first = k == (int)threadIdx.x;
-        float cmax = __uint_as_float(smax[k]);
-        float beta = 1.0f;
-        float wmax = first ? wmax0 : wmax_O[k];
-        if (wmax > 0.0f) beta = fmaxf(1.0f, __builtin_sqrtf(__fdiv_rn(cmax, wmax)));                 // Eq. 8
-        float sp = first ? sprev0 : s_prev[k];
-        float s = __fadd_rn(__fmul_rn(gamma, sp), __fmul_rn(__fsub_rn(1.0f, gamma), beta));         // Eq. 7
-        sm1[k] = __fsub_rn(s, 1.0f);
-        if (blockIdx.x == 0) {
-            s_O[k] = s;
-            colscale[first ? o0 : O[k]] = __fdiv_rn(1.0f, s);
-            if (cmax_out) cmax_out[k] = cmax;
-        }
-    }
-    __syncthreads();
-    if (j >= c_out) return;
-    // what[k, j] for this output channel (Eq. 5), quantized per output channel (Eq. 1)
-    u32x4* dst = reinterpret_cast<u32x4*>(what_int + j * n_pad);
-    float d, c;
-    if (small) {
-        float m = 0.0f;
-#pragma unroll
-        for (int k = 0; k < 64; ++k) {
-            w[k] = k < n ? __fmul_rn(sm1[k < n ? k : n - 1], w[k]) : 0.0f;
-            m = fmaxf(m, fabsf(w[k]));
-        }
-        rtn_steps(m, d, c);
-#pragma unroll
-        for (int k16 = 0; k16 < 64; k16 += 16) {
-            u32x4 q4 = (u32x4){0, 0, 0, 0};
-#pragma unroll
-            for (int u = 0; u < 16; ++u) q4[u >> 2] |= (uint32_t)(rtn_code(w[k16 + u], c) & 0xFF) << (8 * (u & 3));
-            dst[k16 >> 4] = q4;
-        }
-    } else {
-        float m = 0.0f;
-        for (int k = 0; k < n; ++k) m = fmaxf(m, fabsf(__fmul_rn(sm1[k], W_O[(int64_t)k * c_out + j])));
-        rtn_steps(m, d, c);
-        for (int k16 = 0; k16 < n_pad; k16 += 16) {
-            u32x4 q4 = (u32x4){0, 0, 0, 0};
-#pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                int k = k16 + u;
-                int q = 0;
-                if (k < n) q = rtn_code(__fmul_rn(sm1[k], W_O[(int64_t)k * c_out + j]), c);
-                q4[u >> 2] |= (uint32_t)(q & 0xFF) << (8 * (u & 3));
-            }
-            dst[k16 >> 4] = q4;
-        }
-    }
-    delta_what[j] = d;
+    extern __shared__ float sm1[];                                  // [n] : s_k - 1, then [n] maxima
+    momentum_what_body<kWhatThreads, kPartBatch>(blockIdx.x, sm1, part, nslab, n, n_pad, wmax_O, s_prev, gamma, O, s_O,
+                                                 colscale, cmax_out, W_O, c_out, what_int, delta_what);
 }
 
 // Dense variant of the column abs-max for outlier sets that touch most 64-byte segments of a row anyway (the
@@ -208,10 +125,7 @@ momentum_what_wide_kernel(const uint32_t* __restrict__ part, int nslab, int n, i
     __syncthreads();
     for (int k = threadIdx.x; k < n; k += NT) {
         float cmax = __uint_as_float(smax[k]);
-        float beta = 1.0f;
-        float wmax = wmax_O[k];
-        if (wmax > 0.0f) beta = fmaxf(1.0f, __builtin_sqrtf(__fdiv_rn(cmax, wmax)));                       // Eq. 8
-        float s = __fadd_rn(__fmul_rn(gamma, s_prev[k]), __fmul_rn(__fsub_rn(1.0f, gamma), beta));        // Eq. 7
+        float s = momentum_scale(cmax, wmax_O[k], s_prev[k], gamma);
         sm1[k] = __fsub_rn(s, 1.0f);
         if (blockIdx.x == 0) {
             s_O[k] = s;
