@@ -349,7 +349,7 @@ int quaff_bwd_dx_outlier_exact(const uint16_t* dY, int64_t t, int64_t lddy, int6
 size_t quaff_calibrate_workspace_bytes(int64_t c_in, int32_t n_samples) {
     if (c_in <= 0 || n_samples <= 0) return 0;
     return align_up((size_t)n_samples * 8 * c_in * 2) + align_up((size_t)n_samples * 8 * ((c_in + 2047) / 2048) * 8) +
-           align_up((size_t)c_in) + 256;
+           align_up((size_t)c_in * 4) + 256;
 }
 
 int quaff_calibrate_outliers(const uint16_t* X, int64_t t_total, int64_t c_in, int64_t ldx,
@@ -363,13 +363,13 @@ int quaff_calibrate_outliers(const uint16_t* X, int64_t t_total, int64_t c_in, i
         return QUAFF_ERR_SHAPE;
     const size_t cm = align_up((size_t)n_samples * 8 * c_in * 2);              // 8 row slabs per sample
     const size_t ps = align_up((size_t)n_samples * 8 * ((c_in + 2047) / 2048) * 8);
-    if (!workspace || workspace_bytes < cm + ps + align_up((size_t)c_in)) return QUAFF_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes < cm + ps + align_up((size_t)c_in * 4)) return QUAFF_ERR_WORKSPACE;
     if (!aligned16(X) || !aligned16(workspace) || ldx % 8 != 0) return QUAFF_ERR_ALIGN;
     char* base = static_cast<char*>(workspace);
     return hip_status(quaff::launch_calibrate(X, ldx, c_in, t_total, sample_offsets, n_samples, ratio, budget, xi,
                                               budget > 0 ? O : nullptr, n_outlier, reinterpret_cast<uint16_t*>(base),
                                               reinterpret_cast<double*>(base + cm),
-                                              reinterpret_cast<uint8_t*>(base + cm + ps),
+                                              reinterpret_cast<int32_t*>(base + cm + ps),
                                               static_cast<hipStream_t>(stream)));
 }
 

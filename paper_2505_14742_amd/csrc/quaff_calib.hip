@@ -6,8 +6,8 @@
 //                         the sum of magnitudes in fp64;
 //   calib_count_kernel    thresholds ratio * mean per sample (fp64, chunk sums added in a fixed order), then one
 //                         thread per channel counts the samples that exceed theirs;
-//   calib_rank_kernel     one thread per channel ranks it by (xi descending, index ascending) and flags the first
-//   calib_place_kernel    `budget` channels with xi > 0; the flagged channels are then written in ascending order.
+//   calib_rank_kernel     rank of every channel in the order (xi descending, index ascending), summed over slices
+//   calib_place_kernel    the first `budget` channels of that order with xi > 0, written in ascending channel order.
 // The comparison that decides a count is made in fp64 on both sides of the parity test; the fp64 sum of a few
 // million bf16 magnitudes is exact or within an ulp whatever the order, so a decision could only differ for a
 // column maximum within 1e-15 (relative) of the threshold.
@@ -79,7 +79,7 @@ constexpr int kCalibTile = 2048;   // samples whose thresholds are held in LDS a
 __global__ void __launch_bounds__(256)
 calib_count_kernel(const uint16_t* __restrict__ colmax, const double* __restrict__ part_sum, int nchunk,
                    const int64_t* __restrict__ offsets, int64_t t_total, int n_samples, int64_t c_in, double ratio,
-                   int32_t* __restrict__ xi) {
+                   int32_t* __restrict__ xi, int32_t* __restrict__ rank) {
     __shared__ double thr[kCalibTile];
     const int64_t o = (int64_t)blockIdx.x * 256 + threadIdx.x;
     int count = 0;
@@ -108,33 +108,38 @@ calib_count_kernel(const uint16_t* __restrict__ colmax, const double* __restrict
                 count += m > thr[i] ? 1 : 0;
             }
     }
-    if (o < c_in) xi[o] = count;
+    if (o < c_in) {
+        xi[o] = count;
+        rank[o] = 0;   // accumulated by calib_rank_kernel
+    }
 }
 
-// sel[o] = 1 iff channel o is among the `budget` largest xi (ties to the lower index) and xi[o] > 0.
-// One thread per channel; xi is walked through LDS in tiles.
+// rank[o] += number of channels q in this workgroup's 2048-channel slice that precede o in the order
+// (xi descending, index ascending).  One thread per channel and slice; integer atomics, so the sum is exact
+// whatever the order.  rank was zeroed by calib_count_kernel.
 __global__ void __launch_bounds__(256)
-calib_rank_kernel(const int32_t* __restrict__ xi, int c_in, int budget, uint8_t* __restrict__ sel) {
+calib_rank_kernel(const int32_t* __restrict__ xi, int c_in, int32_t* __restrict__ rank) {
     __shared__ int32_t tile[2048];
     const int o = blockIdx.x * 256 + threadIdx.x;
-    const int x = o < c_in ? xi[o] : 0;
-    int rank = 0;
-    for (int q0 = 0; q0 < c_in; q0 += 2048) {
-        const int nq = c_in - q0 < 2048 ? c_in - q0 : 2048;
-        __syncthreads();
-        for (int q = threadIdx.x; q < nq; q += 256) tile[q] = xi[q0 + q];
-        __syncthreads();
-        for (int q = 0; q < nq; ++q) {
-            const int y = tile[q];
-            rank += (y > x || (y == x && q0 + q < o)) ? 1 : 0;
-        }
+    const int q0 = blockIdx.y * 2048;
+    const int nq = c_in - q0 < 2048 ? c_in - q0 : 2048;
+    for (int q = threadIdx.x; q < nq; q += 256) tile[q] = xi[q0 + q];
+    __syncthreads();
+    if (o >= c_in) return;
+    const int x = xi[o];
+    int r = 0;
+    for (int q = 0; q < nq; ++q) {
+        const int y = tile[q];
+        r += (y > x || (y == x && q0 + q < o)) ? 1 : 0;
     }
-    if (o < c_in) sel[o] = (x > 0 && rank < budget) ? 1 : 0;
+    atomicAdd(&rank[o], r);
 }
 
-// O[pos] = o for the selected channels in ascending order, pos = number of selected channels below o
+// Channel o is selected iff xi[o] > 0 and rank[o] < budget.  O[pos] = o for the selected channels in ascending
+// order, pos = number of selected channels below o.
 __global__ void __launch_bounds__(256)
-calib_place_kernel(const uint8_t* __restrict__ sel, int c_in, int32_t* __restrict__ O, int32_t* __restrict__ n_out) {
+calib_place_kernel(const int32_t* __restrict__ xi, const int32_t* __restrict__ rank, int budget, int c_in,
+                   int32_t* __restrict__ O, int32_t* __restrict__ n_out) {
     __shared__ uint8_t tile[4096];
     const int o = blockIdx.x * 256 + threadIdx.x;
     const int last = blockIdx.x * 256 + 255 < c_in - 1 ? blockIdx.x * 256 + 255 : c_in - 1;   // highest channel here
@@ -142,18 +147,20 @@ calib_place_kernel(const uint8_t* __restrict__ sel, int c_in, int32_t* __restric
     for (int q0 = 0; q0 <= last; q0 += 4096) {
         const int nq = c_in - q0 < 4096 ? c_in - q0 : 4096;
         __syncthreads();
-        for (int q = threadIdx.x; q < nq; q += 256) tile[q] = sel[q0 + q];
+        for (int q = threadIdx.x; q < nq; q += 256) tile[q] = (xi[q0 + q] > 0 && rank[q0 + q] < budget) ? 1 : 0;
         __syncthreads();
         const int lim = o - q0 < nq ? o - q0 : nq;     // channels q0 .. min(o, q0 + nq) - 1
         for (int q = 0; q < lim; ++q) pos += tile[q];
     }
-    if (o < c_in && sel[o]) O[pos] = o;
-    if (o == c_in - 1) *n_out = pos + sel[o];
+    if (o >= c_in) return;
+    const int mine = (xi[o] > 0 && rank[o] < budget) ? 1 : 0;
+    if (mine) O[pos] = o;
+    if (o == c_in - 1) *n_out = pos + mine;
 }
 
 hipError_t launch_calibrate(const uint16_t* X, int64_t ldx, int64_t c_in, int64_t t_total, const int64_t* offsets,
                             int32_t n_samples, double ratio, int32_t budget, int32_t* xi, int32_t* O, int32_t* n_out,
-                            uint16_t* colmax, double* part_sum, uint8_t* sel, hipStream_t stream) {
+                            uint16_t* colmax, double* part_sum, int32_t* rank, hipStream_t stream) {
     ProfScope prof(K_CALIB, stream);
     const int nchunk = (int)((c_in + kCalibCols - 1) / kCalibCols);
     hipLaunchKernelGGL(calib_sample_kernel, dim3(nchunk, n_samples, kCalibSlabs), dim3(256), 0, stream, X, ldx, c_in, t_total,
@@ -161,15 +168,16 @@ hipError_t launch_calibrate(const uint16_t* X, int64_t ldx, int64_t c_in, int64_
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(calib_count_kernel, dim3((unsigned)((c_in + 255) / 256)), dim3(256), 0, stream, colmax, part_sum,
-                       nchunk, offsets, t_total, n_samples, c_in, ratio, xi);
+                       nchunk, offsets, t_total, n_samples, c_in, ratio, xi, rank);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (O) {
         const unsigned nb = (unsigned)((c_in + 255) / 256);
-        hipLaunchKernelGGL(calib_rank_kernel, dim3(nb), dim3(256), 0, stream, xi, (int)c_in, budget, sel);
+        hipLaunchKernelGGL(calib_rank_kernel, dim3(nb, (unsigned)((c_in + 2047) / 2048)), dim3(256), 0, stream, xi,
+                           (int)c_in, rank);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(calib_place_kernel, dim3(nb), dim3(256), 0, stream, sel, (int)c_in, O, n_out);
+        hipLaunchKernelGGL(calib_place_kernel, dim3(nb), dim3(256), 0, stream, xi, rank, budget, (int)c_in, O, n_out);
         e = hipGetLastError();
     }
     return e;

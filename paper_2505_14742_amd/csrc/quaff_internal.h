@@ -88,10 +88,10 @@ hipError_t launch_outlier_grad(const uint16_t* dY, int64_t t, int64_t lddy, int6
                                hipStream_t stream);
 
 // Outlier-channel identification (quaff_calib.hip).  Scratch: colmax [n_samples x 8 x c_in] bf16 magnitudes, part_sum
-// [n_samples x 8 x ceil(c_in / 2048)] fp64 (8 row slabs per sample), sel [c_in] bytes.
+// [n_samples x 8 x ceil(c_in / 2048)] fp64 (8 row slabs per sample), rank [c_in] int32.
 hipError_t launch_calibrate(const uint16_t* X, int64_t ldx, int64_t c_in, int64_t t_total, const int64_t* offsets,
                             int32_t n_samples, double ratio, int32_t budget, int32_t* xi, int32_t* O, int32_t* n_out,
-                            uint16_t* colmax, double* part_sum, uint8_t* sel, hipStream_t stream);
+                            uint16_t* colmax, double* part_sum, int32_t* rank, hipStream_t stream);
 
 // Quantizer (colscale = cs, no outlier copy) and LoRA down-projection with a contraction-contiguous factor
 // L [r x c] of the same bf16 matrix X in ONE launch (quaff_quant_lora.hip).  Returns false, with nothing enqueued,
