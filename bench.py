@@ -310,6 +310,36 @@ def main():
         extra["exact_dx_on_outlier_channels"] = {
             "ms_per_step": round(e0.elapsed_time(e1) / args.steps, 5),
             "calls_per_step": "quaff_bwd_dx_outlier_exact per projection (after quaff_linear_bwd_dx)"}
+    # bf16-output variant of the two products (four separate calls; compare with --separate-calls)
+    if all(L["p"].backward and L["p"].c_in % 64 == 0 and L["p"].c_out % 64 == 0 and L["n"] <= 128 for L in layers):
+        for L in layers:
+            L["Y16"] = torch.empty((L["p"].t, L["p"].c_out), dtype=torch.int16, device=dev)
+            L["dX16"] = torch.empty((L["p"].t, L["p"].c_in), dtype=torch.int16, device=dev)
+
+        def step16(i):
+            b = i % args.batches
+            for L in layers:
+                p, n, r = L["p"], L["n"], L["r"]
+                X = L["X"][b]
+                q.scale_update(X, L["O"], L["W_O"], L["wmax"], p.c_out, p.gamma, L["s"], L["cs"], L["what"], L["dwh"],
+                               None, L["ws"])
+                q.quant_act(X, L["cs"], L["O"], L["Xq"], L["dx"], L["xo"] if n else None)
+                q.linear_fwd(L["Xq"], L["dx"], L["xo"] if n else None, L["Wq"], L["dw"], p.c_in, p.c_out,
+                             L["what"] if n else None, L["dwh"] if n else None, n, X if r else None, L["A"], L["B"], r,
+                             p.lora_scale, L["Y16"], L["ws"], bf16_out=True)
+                q.linear_bwd_dx(L["dY"][b], L["Wq"], L["dw"], p.c_in, p.c_out, L["A"], L["B"], r, p.lora_scale,
+                                L["dX16"], L["ws"], bf16_out=True)
+        for i in range(3):
+            step16(i)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(args.steps):
+            step16(i)
+        e1.record()
+        torch.cuda.synchronize()
+        ms16 = e0.elapsed_time(e1) / args.steps
+        extra["bf16_outputs"] = {"ms_per_step": round(ms16, 5), "tops": round(total_ops / (ms16 * 1e-3) / 1e12, 2),
+                                 "calls_per_step": "scale_update, quant_act, linear_fwd_bf16, linear_bwd_dx_bf16"}
     # outlier identification (Eq. 6) on 32 calibration samples of 512 tokens of the first projection's recipe
     p0 = layers[0]["p"]
     ns, rows = 32, 512

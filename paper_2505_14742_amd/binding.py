@@ -29,8 +29,12 @@ SIGNATURES = {
     "quaff_quant_act": (C.c_int, [_vp, _i64, _i64, _i64, _vp, _vp, _i32, _vp, _vp, _vp, _vp]),
     "quaff_linear_fwd": (C.c_int, [_vp, _vp, _vp, _i64, _vp, _vp, _i64, _i64, _vp, _vp, _i32, _vp, _i64, _vp, _vp,
                                    _i32, _f32, _vp, _i64, _vp, _sz, _vp]),
+    "quaff_linear_fwd_bf16": (C.c_int, [_vp, _vp, _vp, _i64, _vp, _vp, _i64, _i64, _vp, _vp, _i32, _vp, _i64, _vp, _vp,
+                                   _i32, _f32, _vp, _i64, _vp, _sz, _vp]),
     "quaff_linear_fwd_acc": (C.c_int, [_vp, _vp, _i64, _vp, _i64, _i64, _vp, _i32, _vp, _vp, _vp]),
     "quaff_linear_bwd_dx": (C.c_int, [_vp, _i64, _i64, _vp, _vp, _i64, _i64, _vp, _vp, _i32, _f32, _vp, _i64, _vp,
+                                      _sz, _vp]),
+    "quaff_linear_bwd_dx_bf16": (C.c_int, [_vp, _i64, _i64, _vp, _vp, _i64, _i64, _vp, _vp, _i32, _f32, _vp, _i64, _vp,
                                       _sz, _vp]),
     "quaff_linear_bwd_dx_acc": (C.c_int, [_vp, _i64, _i64, _vp, _vp, _i64, _i64, _vp, _vp, _vp, _vp]),
     "quaff_lora_bwd_workspace_bytes": (_sz, [_i64, _i64, _i64, _i32]),
@@ -136,9 +140,10 @@ def quant_act(X, colscale, O, Xq, delta, xq_O):
 
 
 def linear_fwd(Xq, delta_x, xq_O, Wq_packed, delta_w, c_in, c_out, what_int, delta_what, n_outlier, X, lora_A, lora_B,
-               lora_rank, lora_scale, Y, workspace):
+               lora_rank, lora_scale, Y, workspace, bf16_out=False):
     t = Xq.shape[0]
-    _check(lib().quaff_linear_fwd(_ptr(Xq), _ptr(delta_x), _ptr(xq_O), t, _ptr(Wq_packed), _ptr(delta_w), c_in, c_out,
+    fn = lib().quaff_linear_fwd_bf16 if bf16_out else lib().quaff_linear_fwd
+    _check(fn(_ptr(Xq), _ptr(delta_x), _ptr(xq_O), t, _ptr(Wq_packed), _ptr(delta_w), c_in, c_out,
                                   _ptr(what_int), _ptr(delta_what), n_outlier, _ptr(X),
                                   0 if X is None else X.stride(0), _ptr(lora_A), _ptr(lora_B), lora_rank,
                                   float(lora_scale), _ptr(Y), Y.stride(0), _ptr(workspace),
@@ -151,9 +156,11 @@ def linear_fwd_acc(Xq, xq_O, Wq_packed, c_in, c_out, what_int, n_outlier, acc1, 
                                       n_outlier, _ptr(acc1), _ptr(acc2), _stream()))
 
 
-def linear_bwd_dx(dY, Wq_packed, delta_w, c_in, c_out, lora_A, lora_B, lora_rank, lora_scale, dX, workspace):
+def linear_bwd_dx(dY, Wq_packed, delta_w, c_in, c_out, lora_A, lora_B, lora_rank, lora_scale, dX, workspace,
+                  bf16_out=False):
     t = dY.shape[0]
-    _check(lib().quaff_linear_bwd_dx(_ptr(dY), t, dY.stride(0), _ptr(Wq_packed), _ptr(delta_w), c_in, c_out,
+    fn = lib().quaff_linear_bwd_dx_bf16 if bf16_out else lib().quaff_linear_bwd_dx
+    _check(fn(_ptr(dY), t, dY.stride(0), _ptr(Wq_packed), _ptr(delta_w), c_in, c_out,
                                      _ptr(lora_A), _ptr(lora_B), lora_rank, float(lora_scale), _ptr(dX), dX.stride(0),
                                      _ptr(workspace),
                                      0 if workspace is None else workspace.numel() * workspace.element_size(),

@@ -175,16 +175,20 @@ static int fwd_common(const int8_t* Xq, const float* delta_x, const int8_t* xq_O
     return QUAFF_OK;
 }
 
-int quaff_linear_fwd(const int8_t* Xq, const float* delta_x, const int8_t* xq_O, int64_t t, const void* Wq_packed,
-                     const float* delta_w, int64_t c_in, int64_t c_out, const int8_t* what_int,
-                     const float* delta_what, int32_t n_outlier, const uint16_t* X, int64_t ldx,
-                     const uint16_t* lora_A, const uint16_t* lora_B, int32_t lora_rank, float lora_scale, float* Y,
-                     int64_t ldy, void* workspace, size_t workspace_bytes, void* stream) {
+// Y32 (fp32) or Y16 (bf16) receives the result
+static int linear_fwd_impl(const int8_t* Xq, const float* delta_x, const int8_t* xq_O, int64_t t, const void* Wq_packed,
+                           const float* delta_w, int64_t c_in, int64_t c_out, const int8_t* what_int,
+                           const float* delta_what, int32_t n_outlier, const uint16_t* X, int64_t ldx,
+                           const uint16_t* lora_A, const uint16_t* lora_B, int32_t lora_rank, float lora_scale,
+                           float* Y, uint16_t* Y16, int64_t ldy, void* workspace, size_t workspace_bytes,
+                           void* stream) {
     quaff::GemmArgs g;
     int st = fwd_common(Xq, delta_x, xq_O, t, Wq_packed, delta_w, c_in, c_out, what_int, delta_what, n_outlier, g);
     if (st != QUAFF_OK) return st;
-    if (!delta_x || !delta_w || !Y || (n_outlier > 0 && !delta_what)) return QUAFF_ERR_NULL;
+    if (!delta_x || !delta_w || (!Y && !Y16) || (n_outlier > 0 && !delta_what)) return QUAFF_ERR_NULL;
     if (!rank_ok(lora_rank) || ldy < c_out) return QUAFF_ERR_SHAPE;
+    if (Y16 && (c_in % 64 != 0 || n_outlier > 128 || ldy % 2 != 0)) return QUAFF_ERR_SHAPE;
+    if (Y16 && (reinterpret_cast<uintptr_t>(Y16) & 3u)) return QUAFF_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (lora_rank > 0) {
         if (!X || !lora_A || !lora_B) return QUAFF_ERR_NULL;
@@ -203,8 +207,29 @@ int quaff_linear_fwd(const int8_t* Xq, const float* delta_x, const int8_t* xq_O,
         if (st != QUAFF_OK) return st;
         g.T_hi = t_hi; g.T_lo = t_lo; g.L = lt; g.r = lora_rank;
     }
-    g.C = Y; g.ldc = ldy;
+    g.C = Y; g.C16 = Y16; g.ldc = ldy;
     return hip_status(quaff::launch_gemm(g, false, s));
+}
+
+int quaff_linear_fwd(const int8_t* Xq, const float* delta_x, const int8_t* xq_O, int64_t t, const void* Wq_packed,
+                     const float* delta_w, int64_t c_in, int64_t c_out, const int8_t* what_int,
+                     const float* delta_what, int32_t n_outlier, const uint16_t* X, int64_t ldx,
+                     const uint16_t* lora_A, const uint16_t* lora_B, int32_t lora_rank, float lora_scale, float* Y,
+                     int64_t ldy, void* workspace, size_t workspace_bytes, void* stream) {
+    return linear_fwd_impl(Xq, delta_x, xq_O, t, Wq_packed, delta_w, c_in, c_out, what_int, delta_what, n_outlier, X,
+                           ldx, lora_A, lora_B, lora_rank, lora_scale, Y, nullptr, ldy, workspace, workspace_bytes,
+                           stream);
+}
+
+int quaff_linear_fwd_bf16(const int8_t* Xq, const float* delta_x, const int8_t* xq_O, int64_t t, const void* Wq_packed,
+                          const float* delta_w, int64_t c_in, int64_t c_out, const int8_t* what_int,
+                          const float* delta_what, int32_t n_outlier, const uint16_t* X, int64_t ldx,
+                          const uint16_t* lora_A, const uint16_t* lora_B, int32_t lora_rank, float lora_scale,
+                          uint16_t* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!Y) return QUAFF_ERR_NULL;
+    return linear_fwd_impl(Xq, delta_x, xq_O, t, Wq_packed, delta_w, c_in, c_out, what_int, delta_what, n_outlier, X,
+                           ldx, lora_A, lora_B, lora_rank, lora_scale, nullptr, Y, ldy, workspace, workspace_bytes,
+                           stream);
 }
 
 int quaff_linear_fwd_acc(const int8_t* Xq, const int8_t* xq_O, int64_t t, const void* Wq_packed, int64_t c_in,
@@ -218,11 +243,13 @@ int quaff_linear_fwd_acc(const int8_t* Xq, const int8_t* xq_O, int64_t t, const 
     return hip_status(quaff::launch_gemm(g, true, static_cast<hipStream_t>(stream)));
 }
 
-int quaff_linear_bwd_dx(const uint16_t* dY, int64_t t, int64_t lddy, const void* Wq_packed, const float* delta_w,
-                        int64_t c_in, int64_t c_out, const uint16_t* lora_A, const uint16_t* lora_B, int32_t lora_rank,
-                        float lora_scale, float* dX, int64_t lddx, void* workspace, size_t workspace_bytes,
-                        void* stream) {
-    if (!dY || !Wq_packed || !delta_w || !dX) return QUAFF_ERR_NULL;
+static int linear_bwd_dx_impl(const uint16_t* dY, int64_t t, int64_t lddy, const void* Wq_packed, const float* delta_w,
+                              int64_t c_in, int64_t c_out, const uint16_t* lora_A, const uint16_t* lora_B,
+                              int32_t lora_rank, float lora_scale, float* dX, uint16_t* dX16, int64_t lddx,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+    if (!dY || !Wq_packed || !delta_w || (!dX && !dX16)) return QUAFF_ERR_NULL;
+    if (dX16 && (c_out % 64 != 0 || lddx % 2 != 0)) return QUAFF_ERR_SHAPE;
+    if (dX16 && (reinterpret_cast<uintptr_t>(dX16) & 3u)) return QUAFF_ERR_ALIGN;
     if (lora_rank > 0 && (!lora_A || !lora_B)) return QUAFF_ERR_NULL;
     if (!dims_ok(t, c_in, c_out) || !rank_ok(lora_rank) || lddy < c_out || lddx < c_in) return QUAFF_ERR_SHAPE;
     BwdWs w = ws_bwd(t, c_out, lora_rank);
@@ -262,8 +289,25 @@ int quaff_linear_bwd_dx(const uint16_t* dY, int64_t t, int64_t lddy, const void*
         st = hip_status(quaff::launch_quant_act(dY, t, c_out, lddy, delta_w, nullptr, 0, gq, dg, nullptr, s));
         if (st != QUAFF_OK) return st;
     }
-    g.C = dX; g.ldc = lddx;
+    g.C = dX; g.C16 = dX16; g.ldc = lddx;
     return hip_status(quaff::launch_gemm(g, false, s));
+}
+
+int quaff_linear_bwd_dx(const uint16_t* dY, int64_t t, int64_t lddy, const void* Wq_packed, const float* delta_w,
+                        int64_t c_in, int64_t c_out, const uint16_t* lora_A, const uint16_t* lora_B, int32_t lora_rank,
+                        float lora_scale, float* dX, int64_t lddx, void* workspace, size_t workspace_bytes,
+                        void* stream) {
+    return linear_bwd_dx_impl(dY, t, lddy, Wq_packed, delta_w, c_in, c_out, lora_A, lora_B, lora_rank, lora_scale, dX,
+                              nullptr, lddx, workspace, workspace_bytes, stream);
+}
+
+int quaff_linear_bwd_dx_bf16(const uint16_t* dY, int64_t t, int64_t lddy, const void* Wq_packed, const float* delta_w,
+                             int64_t c_in, int64_t c_out, const uint16_t* lora_A, const uint16_t* lora_B,
+                             int32_t lora_rank, float lora_scale, uint16_t* dX, int64_t lddx, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+    if (!dX) return QUAFF_ERR_NULL;
+    return linear_bwd_dx_impl(dY, t, lddy, Wq_packed, delta_w, c_in, c_out, lora_A, lora_B, lora_rank, lora_scale,
+                              nullptr, dX, lddx, workspace, workspace_bytes, stream);
 }
 
 int quaff_linear_bwd_dx_acc(const uint16_t* dY, int64_t t, int64_t lddy, const void* Wq_packed, const float* delta_w,

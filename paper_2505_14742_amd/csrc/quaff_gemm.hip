@@ -46,8 +46,9 @@ static hipError_t launch_dma(const GemmArgs& g, bool dump, hipStream_t stream) {
         hipLaunchKernelGGL(k, grid, block, C::LDS_BYTES, stream, g, tm);
     } else if ((int64_t)(g.K2 / 64) * C::K2_PLANES_BYTES <= C::EPI_LIMIT) {
         // the epilogue operands are staged through the idle LDS ring
-        auto k = g.accumulate ? gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, false, MINB, PAIR, true, true>
-                              : gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, false, MINB, PAIR, true, false>;
+        auto k = g.C16          ? gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, false, MINB, PAIR, true, false, true>
+                 : g.accumulate ? gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, false, MINB, PAIR, true, true>
+                                : gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, false, MINB, PAIR, true, false>;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_ALLOC);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, block, C::LDS_ALLOC, stream, g, tm);
@@ -94,6 +95,8 @@ hipError_t launch_gemm(const GemmArgs& g, bool dump_acc, hipStream_t stream) {
     // depending on the tile shape) runs as a launch of its own that writes row_scale * acc2 * col_scale2, and the
     // main product then accumulates onto it: one extra write and read of the output instead of a slow epilogue.
     const bool main_fast = g.K % 64 == 0 && g.M * g.lda < ((int64_t)1 << 32) && g.N * g.ldb < ((int64_t)1 << 32);
+    // bf16 output exists in the fast kernel's single-launch form only
+    if (g.C16 && (!main_fast || g.K2 > 128 || dump_acc)) return hipErrorNotSupported;
     if (!dump_acc && g.K2 > 128 && main_fast) {
         GemmArgs c2{};
         c2.A = g.A2; c2.lda = g.K2; c2.B = g.B2; c2.ldb = g.K2;

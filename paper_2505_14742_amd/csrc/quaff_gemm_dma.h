@@ -228,7 +228,7 @@ __device__ __forceinline__ void gemm_mainloop_dma2(const int8_t* __restrict__ gA
 //   phase B  the low-rank products accumulate onto the fp32 block, 32 columns of r per staging round
 //   phase C  stores (all loads precede all stores: they share one in-order counter)
 // ACCUM adds what C already holds (read in phase A).  The caller guarantees (K2 / 64) * K2_PLANES_BYTES <= EPI_LIMIT.
-template <class C, bool ACCUM>
+template <class C, bool ACCUM, bool OUT16 = false>
 __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (&acc)[C::TM][C::TN],
                                                      lds_i8* __restrict__ dma, const lds_i8* __restrict__ rd,
                                                      int64_t m0, int64_t n0, int wm, int wn, int wave, int lane) {
@@ -387,6 +387,33 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
     }
 
     // ---- phase C
+    if constexpr (OUT16) {
+        // bf16 output (round to nearest even).  A lane holds one column of the block; neighbouring lanes swap half
+        // of their rows so that every lane ends up with two adjacent columns of eight rows and stores 4 bytes at a time.
+        const bool odd = l32 & 1;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int64_t ib = row0 + i * 32;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int64_t jb = col0 + j * 32, col = jb + (l32 & ~1);
+                if (ib >= g.M || jb >= g.N) continue;   // uniform over the wavefront: the swaps below stay convergent
+#pragma unroll
+                for (int p = 0; p < 8; ++p) {
+                    const int mine_keep = acc[i][j][2 * p + (odd ? 1 : 0)];
+                    const int mine_send = acc[i][j][2 * p + (odd ? 0 : 1)];
+                    const int got = __shfl_xor(mine_send, 1, 64);
+                    auto rne = [](int bits) { uint32_t u = (uint32_t)bits; return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16; };
+                    const uint32_t lo = rne(odd ? got : mine_keep), hi = rne(odd ? mine_keep : got);
+                    const int v = 2 * p + (odd ? 1 : 0);
+                    const int64_t row = ib + (v >> 2) * 8 + lhi * 4 + (v & 3);
+                    if (row < g.M && col < g.N)
+                        *reinterpret_cast<uint32_t*>(g.C16 + row * g.ldc + col) = lo | (hi << 16);
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int64_t ib = row0 + i * 32;
@@ -410,7 +437,7 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
 }
 
 template <int BM, int BN, int WGM, int WGN, int STAGES, bool DUMP, int MINB = 1, int PAIR = 0, bool STAGED = false,
-          bool ACCUM = false>
+          bool ACCUM = false, bool OUT16 = false>
 __global__ void __launch_bounds__(64 * WGM * WGN, MINB)
 gemm_i8_dma_kernel(const GemmArgs g, const TileMap tmap) {
     using C = DmaCfg<BM, BN, WGM, WGN, STAGES>;
@@ -459,7 +486,7 @@ gemm_i8_dma_kernel(const GemmArgs g, const TileMap tmap) {
         gemm_mainloop_dma<C>(g.A, g.B, voff, (int)(g.K / C::BK), lds, lds, wave, a_frag_off, b_frag_off, acc);
 
     if constexpr (STAGED && !DUMP)
-        gemm_epilogue_staged<C, ACCUM>(g, acc, lds, lds, m0, n0, wm, wn, wave, lane);
+        gemm_epilogue_staged<C, ACCUM, OUT16>(g, acc, lds, lds, m0, n0, wm, wn, wave, lane);
     else
         gemm_epilogue<C::TM, C::TN, DUMP>(g, acc, m0 + wm * C::WM, n0 + wn * C::WN, l32, lhi);
 }

@@ -132,6 +132,7 @@ struct GemmArgs {
     // (r-contiguous); part p starts M * r elements after part p - 1
     const uint16_t* T_hi; const uint16_t* T_lo; const uint16_t* L; int32_t r;
     float* C; int64_t ldc;         // fp32 output (mode 0)
+    uint16_t* C16;                 // fast kernel only: bf16 output instead of C (same ldc, in elements; not with accumulate)
     int32_t accumulate;            // fast kernel only: add the result to what C already holds instead of overwriting it
                                    // (selects a separate kernel instantiation)
     int32_t* acc1; int32_t* acc2;  // int32 dumps (mode 1), dense ld = N
