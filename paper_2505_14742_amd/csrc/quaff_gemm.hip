@@ -117,15 +117,16 @@ hipError_t launch_gemm_one(const GemmArgs& g, bool dump_acc, hipStream_t stream)
     const int64_t lim32 = (int64_t)1 << 32;
     const bool dma_ok = g.K % 64 == 0 && g.M * g.lda < lim32 && g.N * g.ldb < lim32;
     if (!dma_ok) return launch_generic<128, 128, 64, 2, 2>(g, dump_acc, stream);
-    const bool even_steps = (g.K / 64) % 2 == 0;
+    // contractions that are a multiple of 128 run the wide-stage main loop (128-byte row segments per direct load)
+    const bool wide = g.K % 128 == 0;
     switch (choose_tile(g.M, g.N)) {
-        // the two large shapes consume two contraction steps per barrier when the step count is even
-        case 0: return even_steps ? launch_dma<256, 256, 2, 4, 4, 1, 1>(g, dump_acc, stream)
-                                  : launch_dma<256, 256, 2, 4, 3, 1>(g, dump_acc, stream);
-        case 1: return even_steps ? launch_dma<256, 288, 4, 3, 4, 1, 1>(g, dump_acc, stream)
-                                  : launch_dma<256, 288, 4, 3, 3, 1>(g, dump_acc, stream);
+        case 0: return wide ? launch_dma<256, 256, 2, 4, 4, 1, 2>(g, dump_acc, stream)
+                            : launch_dma<256, 256, 2, 4, 3, 1>(g, dump_acc, stream);
+        case 1: return wide ? launch_dma<256, 288, 4, 3, 4, 1, 2>(g, dump_acc, stream)
+                            : launch_dma<256, 288, 4, 3, 3, 1>(g, dump_acc, stream);
         case 2: return launch_dma<256, 128, 4, 2, 3, 1>(g, dump_acc, stream);
-        default: return launch_dma<128, 192, 2, 2, 4, 2>(g, dump_acc, stream);
+        default: return wide ? launch_dma<128, 192, 2, 2, 4, 2, 2>(g, dump_acc, stream)
+                             : launch_dma<128, 192, 2, 2, 4, 2>(g, dump_acc, stream);
     }
 }
 

@@ -26,6 +26,9 @@ struct DmaCfg {
     static constexpr int NGROUP = (BM + BN) / 16;         // 16-row groups per stage, one direct load (1 KiB) each
     static constexpr int NLOAD = (NGROUP + NW - 1) / NW;  // direct loads per lane per stage
     static constexpr int STAGES_ = STAGES;
+    // wide-stage variant (gemm_mainloop_dma128): 128 contraction bytes per row, one direct load fills 8 rows
+    static constexpr int WSTAGE_BYTES = (BM + BN) * 128, A_WBYTES = BM * 128;
+    static constexpr int NGROUP_W = (BM + BN) / 8, NLOAD_W = (NGROUP_W + NW - 1) / NW;
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
     // epilogue staging (gemm_epilogue_staged): one 64-byte-per-row plane per int8 / bf16 operand below EPI_LIMIT,
     // the fp32 row and column scales in the last SCALE_BYTES of the allocation
@@ -137,35 +140,38 @@ __device__ __forceinline__ void gemm_mainloop_dma(const int8_t* __restrict__ gA,
     QUAFF_WAIT_VMCNT(0);
 }
 
-// Variant of the main loop that consumes TWO 64-byte contraction steps per barrier (ring of four stages): half as
-// many workgroup barriers and counter waits per MFMA.  KT must be even.
+// Wide-stage variant: the ring holds two stages of 128 contraction bytes per row (the same LDS as four 64-byte stages),
+// so that a direct load fetches 128-byte row segments - whole cache lines - instead of 64-byte ones, and one barrier
+// serves two 64-byte contraction steps.  Row r of a stage is 128 bytes, its 16-byte chunk c sits in slot
+// c ^ ((r >> 1) & 7): fragment reads (32 rows x one chunk per half wavefront) are then bank-conflict free.
+// K must be a multiple of 128.
 template <class C>
-__device__ __forceinline__ void gemm_mainloop_dma2(const int8_t* __restrict__ gA, const int8_t* __restrict__ gB,
-                                                   const uint32_t (&voff)[C::NLOAD], int KT,
-                                                   lds_i8* __restrict__ dma, const lds_i8* __restrict__ rd, int wave,
-                                                   int a_frag_off, int b_frag_off, i32x16 (&acc)[C::TM][C::TN]) {
-    constexpr int TM = C::TM, TN = C::TN, NLOAD = C::NLOAD;
-    static_assert(C::STAGES_ == 4, "two steps per barrier need a ring of four stages");
+__device__ __forceinline__ void gemm_mainloop_dma128(const int8_t* __restrict__ gA, const int8_t* __restrict__ gB,
+                                                     const uint32_t (&voff)[C::NLOAD_W], int KT,
+                                                     lds_i8* __restrict__ dma, const lds_i8* __restrict__ rd, int wave,
+                                                     int a_frag_off, int b_frag_off, i32x16 (&acc)[C::TM][C::TN]) {
+    constexpr int TM = C::TM, TN = C::TN, NLOAD = C::NLOAD_W;
+    static_assert(2 * C::WSTAGE_BYTES <= C::LDS_BYTES, "two wide stages must fit the ring");
     auto issue = [&](int tile, int stage) {
-        const int64_t k0 = (int64_t)tile * C::BK;
+        const int64_t k0 = (int64_t)tile * 128;
 #pragma unroll
         for (int j = 0; j < NLOAD; ++j) {
             int q = j * C::NW + wave;
-            if (q >= C::NGROUP) q -= C::NW;
-            const bool isA = q < C::A_BYTES / 1024;
+            if (q >= C::NGROUP_W) q -= C::NW;
+            const bool isA = q < C::BM_ / 8;
             const int8_t* src = (isA ? gA : gB) + k0 + voff[j];
-            lds_i8* dst = dma + stage * C::STAGE_BYTES + q * 1024;
+            lds_i8* dst = dma + stage * C::WSTAGE_BYTES + q * 1024;
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                              (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
         }
     };
     auto read_frags = [&](int stage, int ks, i32x4 (&fa)[TM], i32x4 (&fb)[TN]) {
-        const lds_i8* base = rd + stage * C::STAGE_BYTES;
+        const lds_i8* base = rd + stage * C::WSTAGE_BYTES;
         const int x = ks * 32;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) fa[i] = *(const lds_i32x4*)(base + ((a_frag_off + i * 2048) ^ x));
+        for (int i = 0; i < TM; ++i) fa[i] = *(const lds_i32x4*)(base + ((a_frag_off + i * 4096) ^ x));
 #pragma unroll
-        for (int j = 0; j < TN; ++j) fb[j] = *(const lds_i32x4*)(base + C::A_BYTES + ((b_frag_off + j * 2048) ^ x));
+        for (int j = 0; j < TN; ++j) fb[j] = *(const lds_i32x4*)(base + C::A_WBYTES + ((b_frag_off + j * 4096) ^ x));
     };
     auto mfmas = [&](const i32x4 (&fa)[TM], const i32x4 (&fb)[TN]) {
 #pragma unroll
@@ -179,44 +185,40 @@ __device__ __forceinline__ void gemm_mainloop_dma2(const int8_t* __restrict__ gA
 #pragma unroll
         for (int u = 0; u < TM + TN; ++u) {
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            if (with_loads && u < 2 * NLOAD) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            if (with_loads && u < NLOAD) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_READ, 0);
         }
     };
-
-#pragma unroll
-    for (int s = 0; s < 4; ++s) issue(s < KT ? s : KT - 1, s);
-    QUAFF_WAIT_VMCNT(2 * NLOAD);
+    issue(0, 0);
+    issue(1 < KT ? 1 : KT - 1, 1);
+    QUAFF_WAIT_VMCNT(NLOAD);
     __builtin_amdgcn_s_barrier();
 
     i32x4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
     read_frags(0, 0, fa0, fb0);
-    int s0 = 0;                                   // stage of the first tile of the pair
-    for (int kt = 0; kt < KT; kt += 2) {
-        const int s1 = s0 + 1, s2 = (s0 + 2) & 3;
-        read_frags(s0, 1, fa1, fb1);
+    for (int kt = 0; kt < KT; ++kt) {
+        const int s = kt & 1;
+        read_frags(s, 1, fa1, fb1);
         mfmas(fa0, fb0);
         order_reads(false);
-        read_frags(s1, 0, fa0, fb0);
+        read_frags(s, 2, fa0, fb0);
         mfmas(fa1, fb1);
         order_reads(false);
-        read_frags(s1, 1, fa1, fb1);
+        read_frags(s, 3, fa1, fb1);
         mfmas(fa0, fb0);
         order_reads(false);
-        // both stages of the pair have been read by everyone after this barrier; the next pair must have landed
+        // this stage has been read by everyone after the barrier; the other one must have landed
         QUAFF_WAIT_VMCNT(0);
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         {
-            int t0 = kt + 4, t1 = kt + 5;
-            issue(t0 < KT ? t0 : KT - 1, s0);
-            issue(t1 < KT ? t1 : KT - 1, s1);
+            int t = kt + 2;
+            issue(t < KT ? t : KT - 1, s);
         }
-        read_frags(s2, 0, fa0, fb0);
+        read_frags(s ^ 1, 0, fa0, fb0);
         mfmas(fa1, fb1);
         order_reads(true);
-        s0 = s2;
     }
     QUAFF_WAIT_VMCNT(0);
 }
@@ -454,6 +456,38 @@ gemm_i8_dma_kernel(const GemmArgs g, const TileMap tmap) {
 
     // loader: a direct load fills 16 rows x 64 bytes of a stage (A rows first, then B rows); lane -> (row = lane / 4,
     // slot = lane % 4) and the slot holds global chunk slot ^ ((row / 4) & 3), the swizzle the fragment reads undo
+    if constexpr (PAIR == 2) {
+        // wide stages: a direct load fills 8 rows x 128 bytes; lane -> (row = lane / 8, slot = lane % 8) and the slot
+        // holds global chunk slot ^ ((row >> 1) & 7)
+        uint32_t voffw[C::NLOAD_W];
+#pragma unroll
+        for (int j = 0; j < C::NLOAD_W; ++j) {
+            int q = j * C::NW + wave;
+            if (q >= C::NGROUP_W) q -= C::NW;
+            const bool isA = q < BM / 8;
+            const int local = (isA ? q : q - BM / 8) * 8 + (lane >> 3);
+            const int chunk = (lane & 7) ^ ((local >> 1) & 7);
+            int64_t row = (isA ? m0 : n0) + local;
+            int64_t lim = (isA ? g.M : g.N) - 1;
+            row = row < lim ? row : lim;
+            voffw[j] = (uint32_t)(row * (isA ? g.lda : g.ldb) + chunk * 16);
+        }
+        const int fragw = l32 * 128 + ((lhi ^ ((l32 >> 1) & 7)) * 16);
+        i32x16 accw[C::TM][C::TN];
+#pragma unroll
+        for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+            for (int j = 0; j < C::TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) accw[i][j][v] = 0;
+        gemm_mainloop_dma128<C>(g.A, g.B, voffw, (int)(g.K / 128), lds, lds, wave, wm * C::WM * 128 + fragw,
+                                wn * C::WN * 128 + fragw, accw);
+        if constexpr (STAGED && !DUMP)
+            gemm_epilogue_staged<C, ACCUM, OUT16>(g, accw, lds, lds, m0, n0, wm, wn, wave, lane);
+        else
+            gemm_epilogue<C::TM, C::TN, DUMP>(g, accw, m0 + wm * C::WM, n0 + wn * C::WN, l32, lhi);
+        return;
+    }
     uint32_t voff[C::NLOAD];
     {
         const int r = lane >> 2, chunk = (lane & 3) ^ ((lane >> 4) & 3);
@@ -480,10 +514,7 @@ gemm_i8_dma_kernel(const GemmArgs g, const TileMap tmap) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
-    if constexpr (PAIR)
-        gemm_mainloop_dma2<C>(g.A, g.B, voff, (int)(g.K / C::BK), lds, lds, wave, a_frag_off, b_frag_off, acc);
-    else
-        gemm_mainloop_dma<C>(g.A, g.B, voff, (int)(g.K / C::BK), lds, lds, wave, a_frag_off, b_frag_off, acc);
+    gemm_mainloop_dma<C>(g.A, g.B, voff, (int)(g.K / C::BK), lds, lds, wave, a_frag_off, b_frag_off, acc);
 
     if constexpr (STAGED && !DUMP)
         gemm_epilogue_staged<C, ACCUM, OUT16>(g, acc, lds, lds, m0, n0, wm, wn, wave, lane);
