@@ -65,7 +65,7 @@ struct TileChoice { int bm, bn, spc; double ineff; };
 constexpr TileChoice kChoices[4] = {
     {256, 256, 1, 1.00},   // 8 wavefronts, 128x64 each
     {256, 288, 1, 1.03},   // 12 wavefronts, 64x96 each: 2048 x 9216 outputs are exactly 256 such tiles
-    {256, 128, 2, 1.15},   // 8 wavefronts, 64x64 each
+    {256, 128, 1, 1.18},   // 8 wavefronts, 64x64 each (its wide-stage ring leaves room for one workgroup per unit)
     {128, 192, 2, 1.20},   // 4 wavefronts, 64x96 each: 2048 x 3072 outputs are exactly 256 such tiles
 };
 
@@ -124,7 +124,8 @@ hipError_t launch_gemm_one(const GemmArgs& g, bool dump_acc, hipStream_t stream)
                             : launch_dma<256, 256, 2, 4, 3, 1>(g, dump_acc, stream);
         case 1: return wide ? launch_dma<256, 288, 4, 3, 4, 1, 2>(g, dump_acc, stream)
                             : launch_dma<256, 288, 4, 3, 3, 1>(g, dump_acc, stream);
-        case 2: return launch_dma<256, 128, 4, 2, 3, 1>(g, dump_acc, stream);
+        case 2: return wide ? launch_dma<256, 128, 4, 2, 4, 1, 2>(g, dump_acc, stream)
+                            : launch_dma<256, 128, 4, 2, 3, 1>(g, dump_acc, stream);
         default: return wide ? launch_dma<128, 192, 2, 2, 4, 2, 2>(g, dump_acc, stream)
                              : launch_dma<128, 192, 2, 2, 4, 2>(g, dump_acc, stream);
     }

@@ -151,7 +151,6 @@ __device__ __forceinline__ void gemm_mainloop_dma128(const int8_t* __restrict__ 
                                                      lds_i8* __restrict__ dma, const lds_i8* __restrict__ rd, int wave,
                                                      int a_frag_off, int b_frag_off, i32x16 (&acc)[C::TM][C::TN]) {
     constexpr int TM = C::TM, TN = C::TN, NLOAD = C::NLOAD_W;
-    static_assert(2 * C::WSTAGE_BYTES <= C::LDS_BYTES, "two wide stages must fit the ring");
     auto issue = [&](int tile, int stage) {
         const int64_t k0 = (int64_t)tile * 128;
 #pragma unroll
@@ -189,15 +188,18 @@ __device__ __forceinline__ void gemm_mainloop_dma128(const int8_t* __restrict__ 
             __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_READ, 0);
         }
     };
-    issue(0, 0);
-    issue(1 < KT ? 1 : KT - 1, 1);
-    QUAFF_WAIT_VMCNT(NLOAD);
+    constexpr int NS = C::STAGES_ / 2;            // wide stages in the ring
+    static_assert(NS >= 2 && (NS - 1) * NLOAD < 64, "ring depth / vmcnt range");
+#pragma unroll
+    for (int s = 0; s < NS; ++s) issue(s < KT ? s : KT - 1, s);
+    QUAFF_WAIT_VMCNT((NS - 1) * NLOAD);
     __builtin_amdgcn_s_barrier();
 
     i32x4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
     read_frags(0, 0, fa0, fb0);
+    int s = 0;
     for (int kt = 0; kt < KT; ++kt) {
-        const int s = kt & 1;
+        const int next = s + 1 == NS ? 0 : s + 1;
         read_frags(s, 1, fa1, fb1);
         mfmas(fa0, fb0);
         order_reads(false);
@@ -207,18 +209,19 @@ __device__ __forceinline__ void gemm_mainloop_dma128(const int8_t* __restrict__ 
         read_frags(s, 3, fa1, fb1);
         mfmas(fa0, fb0);
         order_reads(false);
-        // this stage has been read by everyone after the barrier; the other one must have landed
-        QUAFF_WAIT_VMCNT(0);
+        // this stage has been read by everyone after the barrier; the next one must have landed
+        QUAFF_WAIT_VMCNT((NS - 2) * NLOAD);
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         {
-            int t = kt + 2;
+            int t = kt + NS;
             issue(t < KT ? t : KT - 1, s);
         }
-        read_frags(s ^ 1, 0, fa0, fb0);
+        read_frags(next, 0, fa0, fb0);
         mfmas(fa1, fb1);
         order_reads(true);
+        s = next;
     }
     QUAFF_WAIT_VMCNT(0);
 }
