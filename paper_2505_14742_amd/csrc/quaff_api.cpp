@@ -471,8 +471,11 @@ int quaff_linear_fwd_step(const uint16_t* X, int64_t t, int64_t c_in, int64_t ld
     int st = hip_status(quaff::launch_colmax_lora(X, t, c_in, ldx, O, n_outlier, part, s_O, s_prev, nslab, lora_A,
                                                   lora_rank, lora_scale, t_hi, t_lo, lora_B, lt, c_out, s));
     if (st != QUAFF_OK) return st;
+    // The second combined launch pays off while all its workgroups are resident at once (it runs the quantizer at
+    // the requantization role's register budget); long inputs take the two stand-alone kernels.
     hipError_t e = hipSuccess;
-    if (quaff::launch_what_quant(part, nslab, n_outlier, wmax_O, s_prev, gamma, O, s_O, colscale, cmax_out, W_O, c_out,
+    if (t <= 4096 &&
+        quaff::launch_what_quant(part, nslab, n_outlier, wmax_O, s_prev, gamma, O, s_O, colscale, cmax_out, W_O, c_out,
                                  what_int, delta_what, X, t, c_in, ldx, Xq, delta_x, xq_O, s, &e)) {
         if ((st = hip_status(e)) != QUAFF_OK) return st;
     } else {
