@@ -34,13 +34,14 @@ PackedWeight unpack(const void* packed, int64_t c_in, int64_t c_out) {
 
 // workspace layouts -------------------------------------------------------------------------------
 size_t ws_scale(int64_t t, int32_t n) { return align_up(((size_t)quaff::scale_update_blocks(t) * n + n) * sizeof(float)); }
-struct FwdWs { size_t t_hi, t_lo, lt, total; };
-FwdWs ws_fwd(int64_t t, int64_t c_out, int32_t r) {
+struct FwdWs { size_t t_hi, t_lo, lt, at, total; };
+FwdWs ws_fwd(int64_t t, int64_t c_in, int64_t c_out, int32_t r) {
     FwdWs w{};
     size_t off = 0;
     w.t_hi = off; off += align_up((size_t)quaff::kLoraParts * t * r * 2);
     w.t_lo = off; off += align_up((size_t)quaff::kLoraParts * t * r * 2);
     w.lt = off;   off += align_up((size_t)c_out * r * 2);
+    w.at = off;   off += quaff::lora_prefers_transposed(r) ? align_up((size_t)c_in * r * 2) : 0;   // A^T [r x c_in]
     w.total = off;
     return w;
 }
@@ -56,7 +57,7 @@ BwdWs ws_bwd(int64_t t, int64_t c_out, int32_t r) {
     return w;
 }
 
-struct GradWs { size_t t1_hi, t1_lo, t2_hi, t2_lo, p1_hi, p1_lo, p2_hi, p2_lo, part_a, part_b, total; };
+struct GradWs { size_t t1_hi, t1_lo, t2_hi, t2_lo, p1_hi, p1_lo, p2_hi, p2_lo, part_a, part_b, at, total; };
 GradWs ws_grad(int64_t t, int64_t c_in, int64_t c_out, int32_t r) {
     GradWs w{};
     const size_t tbytes = align_up((size_t)quaff::kLoraParts * t * r * 2);
@@ -75,6 +76,7 @@ GradWs ws_grad(int64_t t, int64_t c_in, int64_t c_out, int32_t r) {
     w.p2_lo = off; off += pbytes;
     w.part_a = off; off += align_up((size_t)nslab_a * r * c_in * 4);
     w.part_b = off; off += align_up((size_t)nslab_b * r * c_out * 4);
+    w.at = off; off += quaff::lora_prefers_transposed(r) ? align_up((size_t)c_in * r * 2) : 0;   // A^T [r x c_in]
     w.total = off;
     return w;
 }
@@ -111,7 +113,7 @@ size_t quaff_prepare_workspace_bytes(int64_t c_in, int64_t c_out) {
 
 size_t quaff_workspace_bytes(int64_t t, int64_t c_in, int64_t c_out, int32_t n_outlier, int32_t lora_rank) {
     if (t <= 0 || c_in <= 0 || c_out <= 0 || n_outlier < 0 || lora_rank < 0) return 0;
-    size_t a = ws_scale(t, n_outlier), b = ws_fwd(t, c_out, lora_rank).total, c = ws_bwd(t, c_out, lora_rank).total;
+    size_t a = ws_scale(t, n_outlier), b = ws_fwd(t, c_in, c_out, lora_rank).total, c = ws_bwd(t, c_out, lora_rank).total;
     size_t m = a > b ? a : b;
     return (m > c ? m : c) + 256;
 }
@@ -193,7 +195,7 @@ static int linear_fwd_impl(const int8_t* Xq, const float* delta_x, const int8_t*
     if (lora_rank > 0) {
         if (!X || !lora_A || !lora_B) return QUAFF_ERR_NULL;
         if (ldx < c_in) return QUAFF_ERR_SHAPE;
-        FwdWs w = ws_fwd(t, c_out, lora_rank);
+        FwdWs w = ws_fwd(t, c_in, c_out, lora_rank);
         if (!workspace || workspace_bytes < w.total) return QUAFF_ERR_WORKSPACE;
         if (!aligned16(X) || !aligned16(lora_A) || !aligned16(lora_B) || !aligned16(workspace) || ldx % 8 != 0)
             return QUAFF_ERR_ALIGN;
@@ -203,7 +205,8 @@ static int linear_fwd_impl(const int8_t* Xq, const float* delta_x, const int8_t*
         uint16_t* lt = reinterpret_cast<uint16_t*>(base + w.lt);
         // T = scale * X A (A is [c_in x r]); B [r x c_out] -> B^T [c_out x r] for the epilogue
         st = hip_status(quaff::launch_lora_down(X, t, c_in, ldx, lora_A, false, lora_rank, lora_scale, t_hi, t_lo,
-                                                lora_B, lt, lora_rank, c_out, s));
+                                                lora_B, lt, lora_rank, c_out, s,
+                                                reinterpret_cast<uint16_t*>(base + w.at)));
         if (st != QUAFF_OK) return st;
         g.T_hi = t_hi; g.T_lo = t_lo; g.L = lt; g.r = lora_rank;
     }
@@ -352,7 +355,7 @@ int quaff_lora_bwd_weights(const uint16_t* X, int64_t ldx, const uint16_t* dY, i
                                                 u16(w.t1_lo), nullptr, nullptr, 0, 0, s));
     if (st != QUAFF_OK) return st;
     st = hip_status(quaff::launch_lora_down(X, t, c_in, ldx, lora_A, false, lora_rank, lora_scale, u16(w.t2_hi),
-                                            u16(w.t2_lo), nullptr, nullptr, 0, 0, s));
+                                            u16(w.t2_lo), nullptr, nullptr, 0, 0, s, u16(w.at)));
     if (st != QUAFF_OK) return st;
     st = hip_status(quaff::launch_lora_grad_prep(u16(w.t1_hi), u16(w.t1_lo), u16(w.p1_hi), u16(w.p1_lo), u16(w.t2_hi),
                                                  u16(w.t2_lo), u16(w.p2_hi), u16(w.p2_lo), t, lora_rank, s));
@@ -419,7 +422,7 @@ int quaff_calibrate_outliers(const uint16_t* X, int64_t t_total, int64_t c_in, i
 
 size_t quaff_fwd_step_workspace_bytes(int64_t t, int64_t c_in, int64_t c_out, int32_t n_outlier, int32_t lora_rank) {
     if (t <= 0 || c_in <= 0 || c_out <= 0 || n_outlier < 0 || lora_rank < 0) return 0;
-    return ws_scale(t, n_outlier) + ws_fwd(t, c_out, lora_rank).total + 256;
+    return ws_scale(t, n_outlier) + ws_fwd(t, c_in, c_out, lora_rank).total + 256;
 }
 
 int quaff_linear_fwd_step(const uint16_t* X, int64_t t, int64_t c_in, int64_t ldx, const int32_t* O, int32_t n_outlier,
@@ -430,7 +433,7 @@ int quaff_linear_fwd_step(const uint16_t* X, int64_t t, int64_t c_in, int64_t ld
                           int64_t ldy, void* workspace, size_t workspace_bytes, void* stream) {
     if (t <= 0 || c_in <= 0 || c_out <= 0 || n_outlier < 0 || !rank_ok(lora_rank)) return QUAFF_ERR_SHAPE;
     const size_t scale_bytes = ws_scale(t, n_outlier);
-    if (!workspace || workspace_bytes < scale_bytes + ws_fwd(t, c_out, lora_rank).total) return QUAFF_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes < scale_bytes + ws_fwd(t, c_in, c_out, lora_rank).total) return QUAFF_ERR_WORKSPACE;
     if (!aligned16(workspace)) return QUAFF_ERR_ALIGN;
     if (!colscale) return QUAFF_ERR_NULL;
     if (n_outlier > 0 && !xq_O) return QUAFF_ERR_NULL;
@@ -463,13 +466,14 @@ int quaff_linear_fwd_step(const uint16_t* X, int64_t t, int64_t c_in, int64_t ld
     const int nslab = quaff::scale_update_gather_slabs(t, n_outlier);
     uint32_t* part = reinterpret_cast<uint32_t*>(wsf);
     float* s_prev = wsf + (int64_t)nslab * n_outlier;
-    FwdWs w = ws_fwd(t, c_out, lora_rank);
+    FwdWs w = ws_fwd(t, c_in, c_out, lora_rank);
     char* lin = static_cast<char*>(ws_lin);
     uint16_t* t_hi = reinterpret_cast<uint16_t*>(lin + w.t_hi);
     uint16_t* t_lo = reinterpret_cast<uint16_t*>(lin + w.t_lo);
     uint16_t* lt = reinterpret_cast<uint16_t*>(lin + w.lt);
     int st = hip_status(quaff::launch_colmax_lora(X, t, c_in, ldx, O, n_outlier, part, s_O, s_prev, nslab, lora_A,
-                                                  lora_rank, lora_scale, t_hi, t_lo, lora_B, lt, c_out, s));
+                                                  lora_rank, lora_scale, t_hi, t_lo, lora_B, lt, c_out, s,
+                                                  reinterpret_cast<uint16_t*>(lin + w.at)));
     if (st != QUAFF_OK) return st;
     // The second combined launch pays off while all its workgroups are resident at once (it runs the quantizer at
     // the requantization role's register budget); long inputs take the two stand-alone kernels.

@@ -6,7 +6,7 @@
 
 namespace quaff {
 
-template <int R16>
+template <int R16, bool L_RC>
 __global__ void __launch_bounds__(64 * kLoraWaves)
 colmax_lora_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx, const int32_t* __restrict__ O, int n,
                    uint32_t* __restrict__ part, const float* __restrict__ s_O, float* __restrict__ s_prev, int nslab,
@@ -16,7 +16,7 @@ colmax_lora_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx
     extern __shared__ uint32_t smax[];   // [n]
     const int lora_blocks = lora_nbx * kLoraParts;
     if ((int)blockIdx.x < lora_blocks)
-        lora_down_body<R16, false>(blockIdx.x % lora_nbx, blockIdx.x / lora_nbx, lora_nbx, X, t, c, ldx, L, scale, T_hi,
+        lora_down_body<R16, L_RC>(blockIdx.x % lora_nbx, blockIdx.x / lora_nbx, lora_nbx, X, t, c, ldx, L, scale, T_hi,
                                    T_lo, row_blocks, tr_src, tr_dst, tr_rows, tr_cols);
     else
         colmax_outlier_body<64 * kLoraWaves>(blockIdx.x - lora_blocks, nslab, smax, X, t, ldx, O, n, part, s_O, s_prev);
@@ -26,8 +26,14 @@ colmax_lora_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx
 hipError_t launch_colmax_lora(const uint16_t* X, int64_t t, int64_t c, int64_t ldx, const int32_t* O, int32_t n,
                               uint32_t* part, const float* s_O, float* s_prev, int nslab, const uint16_t* A, int32_t r,
                               float scale, uint16_t* T_hi, uint16_t* T_lo, const uint16_t* B, uint16_t* Bt,
-                              int64_t c_out, hipStream_t stream) {
+                              int64_t c_out, hipStream_t stream, uint16_t* At_scratch) {
     ProfScope prof(K_COLMAX_LORA, stream);
+    const bool transposed = At_scratch && lora_prefers_transposed(r);
+    if (transposed) {
+        hipError_t e = launch_transpose_bf16(A, c, r, At_scratch, stream);
+        if (e != hipSuccess) return e;
+        A = At_scratch;
+    }
     const int row_blocks = (int)((t + 15) / 16);
     int64_t b = ((int64_t)r * c_out + 2047) / 2048;
     const int tr_blocks = (int)(b < 128 ? (b > 0 ? b : 1) : 128);
@@ -35,9 +41,14 @@ hipError_t launch_colmax_lora(const uint16_t* X, int64_t t, int64_t c, int64_t l
     dim3 grid((unsigned)(lora_nbx * kLoraParts + nslab));
 #define QUAFF_CL(N)                                                                                                   \
     case N:                                                                                                           \
-        hipLaunchKernelGGL((colmax_lora_kernel<N>), grid, dim3(64 * kLoraWaves), n * sizeof(uint32_t), stream, X, t,   \
-                           (int)c, ldx, O, n, part, s_O, s_prev, nslab, A, scale, T_hi, T_lo, row_blocks, lora_nbx, B, \
-                           Bt, (int64_t)r, c_out);                                                                     \
+        if (transposed)                                                                                               \
+            hipLaunchKernelGGL((colmax_lora_kernel<N, true>), grid, dim3(64 * kLoraWaves), n * sizeof(uint32_t),      \
+                               stream, X, t, (int)c, ldx, O, n, part, s_O, s_prev, nslab, A, scale, T_hi, T_lo,       \
+                               row_blocks, lora_nbx, B, Bt, (int64_t)r, c_out);                                       \
+        else                                                                                                          \
+            hipLaunchKernelGGL((colmax_lora_kernel<N, false>), grid, dim3(64 * kLoraWaves), n * sizeof(uint32_t),     \
+                               stream, X, t, (int)c, ldx, O, n, part, s_O, s_prev, nslab, A, scale, T_hi, T_lo,       \
+                               row_blocks, lora_nbx, B, Bt, (int64_t)r, c_out);                                       \
         break;
     switch (r / 16) {
         QUAFF_CL(1) QUAFF_CL(2) QUAFF_CL(3) QUAFF_CL(4)

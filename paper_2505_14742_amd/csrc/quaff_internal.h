@@ -67,7 +67,11 @@ hipError_t launch_quant_act(const uint16_t* X, int64_t t, int64_t c, int64_t ldx
 // optional transposed copy of a second factor (src [rows x cols] -> dst [cols x rows]).
 hipError_t launch_lora_down(const uint16_t* X, int64_t t, int64_t c, int64_t ldx, const uint16_t* L, bool L_is_r_by_c,
                             int32_t r, float scale, uint16_t* T_hi, uint16_t* T_lo, const uint16_t* tr_src,
-                            uint16_t* tr_dst, int64_t tr_rows, int64_t tr_cols, hipStream_t stream);
+                            uint16_t* tr_dst, int64_t tr_rows, int64_t tr_cols, hipStream_t stream,
+                            uint16_t* Lt_scratch = nullptr);
+// A [c x r] factor of this rank is better transposed once to [r x c] (scratch of c * r elements) than slice by slice
+inline bool lora_prefers_transposed(int32_t r) { return r >= 32; }
+hipError_t launch_transpose_bf16(const uint16_t* src, int64_t rows, int64_t cols, uint16_t* dst, hipStream_t stream);
 
 // LoRA weight gradients (quaff_lora_grad.hip).  lora_grad_plan: how the token range is cut into slabs (workspace
 // sizing); prep: fold the hi/lo parts of two down-projections into token-contiguous [r x t_pad] pairs;
@@ -106,7 +110,7 @@ int scale_update_gather_slabs(int64_t t, int32_t n);   // slab count the gather 
 hipError_t launch_colmax_lora(const uint16_t* X, int64_t t, int64_t c, int64_t ldx, const int32_t* O, int32_t n,
                               uint32_t* part, const float* s_O, float* s_prev, int nslab, const uint16_t* A, int32_t r,
                               float scale, uint16_t* T_hi, uint16_t* T_lo, const uint16_t* B, uint16_t* Bt,
-                              int64_t c_out, hipStream_t stream);
+                              int64_t c_out, hipStream_t stream, uint16_t* At_scratch = nullptr);
 hipError_t launch_momentum(const uint32_t* part, int nslab, int n, int n_pad, const float* wmax_O, const float* s_prev,
                            float gamma, const int32_t* O, float* s_O, float* colscale, float* cmax_out,
                            const float* W_O, int64_t c_out, int8_t* what_int, float* delta_what, hipStream_t stream);

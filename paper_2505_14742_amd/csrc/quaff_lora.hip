@@ -38,10 +38,36 @@ static void dispatch(int R16, dim3 grid, hipStream_t stream, const uint16_t* X, 
 #undef QUAFF_LORA
 }
 
+// dst [cols x rows] <- src [rows x cols] (bf16), consecutive threads write consecutive addresses
+__global__ void __launch_bounds__(256)
+transpose_bf16_kernel(const uint16_t* __restrict__ src, int64_t rows, int64_t cols, uint16_t* __restrict__ dst) {
+    const int64_t total = rows * cols;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+        const int64_t col = e / rows, row = e % rows;
+        dst[e] = src[row * cols + col];
+    }
+}
+
+hipError_t launch_transpose_bf16(const uint16_t* src, int64_t rows, int64_t cols, uint16_t* dst, hipStream_t stream) {
+    int64_t blocks = (rows * cols + 255) / 256;
+    hipLaunchKernelGGL(transpose_bf16_kernel, dim3((unsigned)(blocks < 1024 ? blocks : 1024)), dim3(256), 0, stream, src,
+                       rows, cols, dst);
+    return hipGetLastError();
+}
+
 hipError_t launch_lora_down(const uint16_t* X, int64_t t, int64_t c, int64_t ldx, const uint16_t* L, bool L_is_r_by_c,
                             int32_t r, float scale, uint16_t* T_hi, uint16_t* T_lo, const uint16_t* tr_src,
-                            uint16_t* tr_dst, int64_t tr_rows, int64_t tr_cols, hipStream_t stream) {
+                            uint16_t* tr_dst, int64_t tr_rows, int64_t tr_cols, hipStream_t stream,
+                            uint16_t* Lt_scratch) {
     ProfScope prof(K_LORA, stream);
+    if (!L_is_r_by_c && Lt_scratch && lora_prefers_transposed(r)) {
+        // a [c x r] factor of rank 32 or more is transposed once (r x c, contraction-contiguous) instead of slice by
+        // slice through LDS inside the product: one small launch more, a several times faster product
+        hipError_t e = launch_transpose_bf16(L, c, r, Lt_scratch, stream);
+        if (e != hipSuccess) return e;
+        L = Lt_scratch;
+        L_is_r_by_c = true;
+    }
     int row_blocks = (int)((t + 15) / 16);
     int tr_blocks = 0;
     if (tr_src) {

@@ -46,7 +46,7 @@ def test_fwd_step_edge_cases(idx):
     _compare(W, O, A if has else None, B if has else None, 0.5, [X, X2, X], 0.2, "edge " + ec.name)
 
 
-@pytest.mark.parametrize("cfg,name", [(1, "single"), (2, "qkv"), (2, "o_proj"), (3, "down"), (4, "q"), (6, "down")])
+@pytest.mark.parametrize("cfg,name", [(1, "single"), (2, "qkv"), (2, "o_proj"), (3, "down"), (4, "q"), (5, "q"), (6, "down")])
 def test_fwd_step_workloads(cfg, name):
     p = synth.projection(cfg, name)
     A, B = synth.lora(p)
