@@ -16,9 +16,17 @@ quant_lora_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx,
     if ((int)blockIdx.x < lora_blocks)
         lora_down_body<R16, true>(blockIdx.x % row_blocks, blockIdx.x / row_blocks, row_blocks, X, t, c, ldx, L, scale,
                                   T_hi, T_lo, row_blocks, nullptr, nullptr, 0, 0);
-    else
-        quant_rows_body<64 * kLoraWaves, TPR, NV>(blockIdx.x - lora_blocks, X, t, c, ldx, cs, nullptr, 0, 0, Xq, delta,
+    else {
+        // The hardware deals consecutive workgroups to the eight XCDs in turn and every XCD has its own L2: the
+        // quantizing workgroups of a 16-row block are renumbered so that they land on the XCD whose down-projection
+        // workgroups (index = row block, same residue modulo 8) read the same rows at about the same time.
+        constexpr int QPG = 16 / ((64 * kLoraWaves) / TPR);   // quantizing workgroups per 16-row block (1 or 4)
+        const int local = blockIdx.x - lora_blocks;
+        const int xcd = local & 7, m = local >> 3;
+        const int rb = (m / QPG) * 8 + xcd;                   // row block
+        quant_rows_body<64 * kLoraWaves, TPR, NV>(rb * QPG + m % QPG, X, t, c, ldx, cs, nullptr, 0, 0, Xq, delta,
                                                   nullptr);
+    }
 }
 
 template <int R16>
@@ -29,7 +37,8 @@ static bool launch_r(const uint16_t* X, int64_t t, int c, int64_t ldx, const flo
     const int vec = (c + 7) / 8;
 #define QUAFF_QL(TPR, NV)                                                                                             \
     hipLaunchKernelGGL((quant_lora_kernel<R16, TPR, NV>),                                                             \
-                       dim3((unsigned)(row_blocks * kLoraParts + (t + NT / TPR - 1) / (NT / TPR))), dim3(NT), 0,      \
+                       dim3((unsigned)(row_blocks * kLoraParts + 8 * ((row_blocks + 7) / 8) * (16 / (NT / TPR)))),   \
+                       dim3(NT), 0,                                                                                   \
                        stream, X, t, c, ldx, cs, Xq, delta, L, scale, T_hi, T_lo, row_blocks)
     if (vec <= 64 * 2) QUAFF_QL(64, 2);
     else if (vec <= 64 * 4) QUAFF_QL(64, 4);
