@@ -154,8 +154,8 @@ int quaff_linear_fwd_step(const uint16_t* X, int64_t t, int64_t c_in, int64_t ld
 
 /* quaff_linear_fwd with the result rounded (to nearest even) to bf16 instead of stored as fp32: the output write,
  * which a launch cannot overlap with anything at a few thousand tokens, is halved.  Everything up to the final
- * rounding is the same arithmetic.  Restrictions: c_in a multiple of 64, n_outlier <= 128, ldy even, Y 4-byte
- * aligned (QUAFF_ERR_SHAPE / QUAFF_ERR_ALIGN otherwise). */
+ * rounding is the same arithmetic.  Restrictions: c_in a multiple of 64, n_outlier <= 128 (QUAFF_ERR_SHAPE
+ * otherwise); Y 16-byte aligned, ldy a multiple of 8 (QUAFF_ERR_ALIGN otherwise). */
 int quaff_linear_fwd_bf16(const int8_t* Xq, const float* delta_x, const int8_t* xq_O, int64_t t, const void* Wq_packed,
                           const float* delta_w, int64_t c_in, int64_t c_out, const int8_t* what_int,
                           const float* delta_what, int32_t n_outlier, const uint16_t* X, int64_t ldx,
@@ -184,8 +184,8 @@ int quaff_linear_bwd_dx(const uint16_t* dY, int64_t t, int64_t lddy, const void*
                         int32_t lora_rank, float lora_scale, float* dX, int64_t lddx, void* workspace,
                         size_t workspace_bytes, void* stream);
 
-/* quaff_linear_bwd_dx with dX rounded (to nearest even) to bf16.  Restrictions: c_out a multiple of 64, lddx even,
- * dX 4-byte aligned. */
+/* quaff_linear_bwd_dx with dX rounded (to nearest even) to bf16.  Restrictions: c_out a multiple of 64; dX 16-byte
+ * aligned, lddx a multiple of 8. */
 int quaff_linear_bwd_dx_bf16(const uint16_t* dY, int64_t t, int64_t lddy, const void* Wq_packed, const float* delta_w,
                              int64_t c_in, int64_t c_out, const uint16_t* lora_A, const uint16_t* lora_B,
                              int32_t lora_rank, float lora_scale, uint16_t* dX, int64_t lddx, void* workspace,

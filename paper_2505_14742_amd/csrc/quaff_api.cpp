@@ -189,8 +189,8 @@ static int linear_fwd_impl(const int8_t* Xq, const float* delta_x, const int8_t*
     if (st != QUAFF_OK) return st;
     if (!delta_x || !delta_w || (!Y && !Y16) || (n_outlier > 0 && !delta_what)) return QUAFF_ERR_NULL;
     if (!rank_ok(lora_rank) || ldy < c_out) return QUAFF_ERR_SHAPE;
-    if (Y16 && (c_in % 64 != 0 || n_outlier > 128 || ldy % 2 != 0)) return QUAFF_ERR_SHAPE;
-    if (Y16 && (reinterpret_cast<uintptr_t>(Y16) & 3u)) return QUAFF_ERR_ALIGN;
+    if (Y16 && (c_in % 64 != 0 || n_outlier > 128)) return QUAFF_ERR_SHAPE;
+    if (Y16 && (!aligned16(Y16) || ldy % 8 != 0)) return QUAFF_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (lora_rank > 0) {
         if (!X || !lora_A || !lora_B) return QUAFF_ERR_NULL;
@@ -251,8 +251,8 @@ static int linear_bwd_dx_impl(const uint16_t* dY, int64_t t, int64_t lddy, const
                               int32_t lora_rank, float lora_scale, float* dX, uint16_t* dX16, int64_t lddx,
                               void* workspace, size_t workspace_bytes, void* stream) {
     if (!dY || !Wq_packed || !delta_w || (!dX && !dX16)) return QUAFF_ERR_NULL;
-    if (dX16 && (c_out % 64 != 0 || lddx % 2 != 0)) return QUAFF_ERR_SHAPE;
-    if (dX16 && (reinterpret_cast<uintptr_t>(dX16) & 3u)) return QUAFF_ERR_ALIGN;
+    if (dX16 && c_out % 64 != 0) return QUAFF_ERR_SHAPE;
+    if (dX16 && (!aligned16(dX16) || lddx % 8 != 0)) return QUAFF_ERR_ALIGN;
     if (lora_rank > 0 && (!lora_A || !lora_B)) return QUAFF_ERR_NULL;
     if (!dims_ok(t, c_in, c_out) || !rank_ok(lora_rank) || lddy < c_out || lddx < c_in) return QUAFF_ERR_SHAPE;
     BwdWs w = ws_bwd(t, c_out, lora_rank);

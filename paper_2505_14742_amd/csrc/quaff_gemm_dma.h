@@ -393,29 +393,49 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
 
     // ---- phase C
     if constexpr (OUT16) {
-        // bf16 output (round to nearest even).  A lane holds one column of the block; neighbouring lanes swap half
-        // of their rows so that every lane ends up with two adjacent columns of eight rows and stores 4 bytes at a time.
+        // bf16 output (round to nearest even).  A 32x32 block is only 64 bytes wide in bf16, so the wavefront's
+        // 32 x WN strip is first assembled in a private piece of the idle LDS ring (neighbouring lanes swap half of
+        // their rows so that a lane writes two adjacent columns as one 32-bit word) and then leaves as 16-byte
+        // stores that cover whole WN * 2-byte row segments.
+        constexpr int ROWB = C::WN * 2, STRIP = 32 * ROWB, CPR = C::WN / 8;   // bytes per row / strip, 16-byte chunks per row
+        static_assert(C::NW * STRIP <= C::LDS_BYTES, "output strips must fit the ring");
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();            // every wavefront is done reading the staged operands
+        asm volatile("" ::: "memory");
+        lds_i8* strip_w = dma + wave * STRIP;
+        const lds_i8* strip_r = rd + wave * STRIP;
         const bool odd = l32 & 1;
+        auto rne = [](int bits) { uint32_t u = (uint32_t)bits; return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16; };
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int64_t ib = row0 + i * 32;
+            if (ib >= g.M) continue;             // uniform over the wavefront
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                const int64_t jb = col0 + j * 32, col = jb + (l32 & ~1);
-                if (ib >= g.M || jb >= g.N) continue;   // uniform over the wavefront: the swaps below stay convergent
 #pragma unroll
                 for (int p = 0; p < 8; ++p) {
                     const int mine_keep = acc[i][j][2 * p + (odd ? 1 : 0)];
                     const int mine_send = acc[i][j][2 * p + (odd ? 0 : 1)];
                     const int got = __shfl_xor(mine_send, 1, 64);
-                    auto rne = [](int bits) { uint32_t u = (uint32_t)bits; return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16; };
                     const uint32_t lo = rne(odd ? got : mine_keep), hi = rne(odd ? mine_keep : got);
                     const int v = 2 * p + (odd ? 1 : 0);
-                    const int64_t row = ib + (v >> 2) * 8 + lhi * 4 + (v & 3);
-                    if (row < g.M && col < g.N)
-                        *reinterpret_cast<uint32_t*>(g.C16 + row * g.ldc + col) = lo | (hi << 16);
+                    const int row = (v >> 2) * 8 + lhi * 4 + (v & 3);
+                    *(__attribute__((address_space(3))) uint32_t*)(strip_w + row * ROWB + (j * 32 + (l32 & ~1)) * 2) =
+                        lo | (hi << 16);
                 }
             }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int it = 0; it < (32 * CPR + 63) / 64; ++it) {
+                const int q = it * 64 + lane;
+                const int row = q / CPR, c16 = q % CPR;
+                if (q < 32 * CPR) {
+                    const i32x4 val = *(const lds_i32x4*)(strip_r + row * ROWB + c16 * 16);
+                    const int64_t grow = ib + row, gcol = col0 + c16 * 8;
+                    if (grow < g.M && gcol < g.N) *reinterpret_cast<i32x4*>(g.C16 + grow * g.ldc + gcol) = val;
+                }
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the strip is reused by the next block row
         }
         return;
     }
