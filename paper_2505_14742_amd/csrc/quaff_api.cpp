@@ -361,11 +361,10 @@ int quaff_lora_bwd_weights(const uint16_t* X, int64_t ldx, const uint16_t* dY, i
                                                  u16(w.t2_lo), u16(w.p2_hi), u16(w.p2_lo), t, lora_rank, s));
     if (st != QUAFF_OK) return st;
     // dA^T [r x c_in] = T1^T X, stored transposed;  dB [r x c_out] = T2^T dY
-    st = hip_status(quaff::launch_lora_grad(X, ldx, t, c_in, u16(w.p1_hi), u16(w.p1_lo), lora_rank,
-                                            reinterpret_cast<float*>(base + w.part_a), dA, true, s));
-    if (st != QUAFF_OK) return st;
-    return hip_status(quaff::launch_lora_grad(dY, lddy, t, c_out, u16(w.p2_hi), u16(w.p2_lo), lora_rank,
-                                              reinterpret_cast<float*>(base + w.part_b), dB, false, s));
+    return hip_status(quaff::launch_lora_grad_pair(X, ldx, c_in, u16(w.p1_hi), u16(w.p1_lo),
+                                                   reinterpret_cast<float*>(base + w.part_a), dA, dY, lddy, c_out,
+                                                   u16(w.p2_hi), u16(w.p2_lo),
+                                                   reinterpret_cast<float*>(base + w.part_b), dB, t, lora_rank, s));
 }
 
 size_t quaff_bwd_dx_outlier_workspace_bytes(int64_t t, int64_t c_out) {

@@ -75,14 +75,15 @@ hipError_t launch_transpose_bf16(const uint16_t* src, int64_t rows, int64_t cols
 
 // LoRA weight gradients (quaff_lora_grad.hip).  lora_grad_plan: how the token range is cut into slabs (workspace
 // sizing); prep: fold the hi/lo parts of two down-projections into token-contiguous [r x t_pad] pairs;
-// launch_lora_grad: out [r x c] (or [c x r] when transposed) = sum_i P[i, :]^T Q[i, :], partial [nslab x r x c] scratch.
+// launch_lora_grad_pair: both gradient products (out = sum_i P[i, :]^T Q[i, :], partial [nslab x r x c] scratch each).
 void lora_grad_plan(int64_t t, int64_t c, int* nslab, int* rows_per_slab);
 hipError_t launch_lora_grad_prep(const uint16_t* T1_hi, const uint16_t* T1_lo, uint16_t* Pt1_hi, uint16_t* Pt1_lo,
                                  const uint16_t* T2_hi, const uint16_t* T2_lo, uint16_t* Pt2_hi, uint16_t* Pt2_lo,
                                  int64_t t, int32_t r, hipStream_t stream);
-hipError_t launch_lora_grad(const uint16_t* Q, int64_t ldq, int64_t t, int64_t c, const uint16_t* Pt_hi,
-                            const uint16_t* Pt_lo, int32_t r, float* partial, float* out, bool transposed,
-                            hipStream_t stream);
+hipError_t launch_lora_grad_pair(const uint16_t* X, int64_t ldx, int64_t c_in, const uint16_t* Pt1_hi,
+                                 const uint16_t* Pt1_lo, float* partial_a, float* dA, const uint16_t* dY, int64_t lddy,
+                                 int64_t c_out, const uint16_t* Pt2_hi, const uint16_t* Pt2_lo, float* partial_b,
+                                 float* dB, int64_t t, int32_t r, hipStream_t stream);
 
 // Full-precision dX on the outlier channels (quaff_outlier_grad.hip).  Scratch: L [64 x c_out] bf16,
 // T_hi / T_lo [kLoraParts x t x 64] bf16.

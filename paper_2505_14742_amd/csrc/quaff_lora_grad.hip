@@ -69,11 +69,27 @@ lora_grad_prep_kernel(PrepArgs a, int64_t t, int64_t t_pad, int r) {
 }
 
 // partial[slab][p][j] = sum over the slab's tokens i of P[i, p] Q[i, j]
+// one of the two products of a launch (blockIdx.z selects it)
+struct GradProblem {
+    const uint16_t* Q; int64_t ldq; int c;
+    const uint16_t* Pt_hi; const uint16_t* Pt_lo;
+    int rows_per_slab, nslab, chunks;
+    float* partial; float* out; int transposed;
+};
+struct GradPair { GradProblem p[2]; };
+
 template <int R16>
 __global__ void __launch_bounds__(256)
-lora_grad_kernel(const uint16_t* __restrict__ Q, int64_t ldq, int64_t t, int c, const uint16_t* __restrict__ Pt_hi,
-                 const uint16_t* __restrict__ Pt_lo, int64_t t_pad, int rows_per_slab, float* __restrict__ partial) {
+lora_grad_kernel(GradPair pair, int64_t t, int64_t t_pad) {
     constexpr int r = R16 * 16;
+    const GradProblem& pb = pair.p[blockIdx.z];
+    if ((int)blockIdx.x >= pb.chunks || (int)blockIdx.y >= pb.nslab) return;
+    const uint16_t* __restrict__ Q = pb.Q;
+    const int64_t ldq = pb.ldq;
+    const int c = pb.c, rows_per_slab = pb.rows_per_slab;
+    const uint16_t* __restrict__ Pt_hi = pb.Pt_hi;
+    const uint16_t* __restrict__ Pt_lo = pb.Pt_lo;
+    float* __restrict__ partial = pb.partial;
     __shared__ __attribute__((aligned(16))) uint8_t tile[32 * kGradRowBytes];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, g = lane >> 4;
@@ -154,8 +170,11 @@ lora_grad_kernel(const uint16_t* __restrict__ Q, int64_t ldq, int64_t t, int c, 
 
 // out = sum over slabs (fixed order) of partial[slab]; transposed = write out[j][p] instead of out[p][j]
 __global__ void __launch_bounds__(256)
-lora_grad_reduce_kernel(const float* __restrict__ partial, int nslab, int r, int c, float* __restrict__ out,
-                        int transposed) {
+lora_grad_reduce_kernel(GradPair pair, int r) {
+    const GradProblem& pb = pair.p[blockIdx.y];
+    const float* __restrict__ partial = pb.partial;
+    float* __restrict__ out = pb.out;
+    const int nslab = pb.nslab, c = pb.c, transposed = pb.transposed;
     const int64_t total = (int64_t)r * c;
     for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
         // consecutive threads take consecutive output addresses
@@ -178,18 +197,30 @@ hipError_t launch_lora_grad_prep(const uint16_t* T1_hi, const uint16_t* T1_lo, u
     return hipGetLastError();
 }
 
-hipError_t launch_lora_grad(const uint16_t* Q, int64_t ldq, int64_t t, int64_t c, const uint16_t* Pt_hi,
-                            const uint16_t* Pt_lo, int32_t r, float* partial, float* out, bool transposed,
-                            hipStream_t stream) {
+// Both gradient products of a layer in one launch each (product, then slab reduction):
+//   dA^T [r x c_in] = P1^T X (stored transposed as dA [c_in x r]),   dB [r x c_out] = P2^T dY
+hipError_t launch_lora_grad_pair(const uint16_t* X, int64_t ldx, int64_t c_in, const uint16_t* Pt1_hi,
+                                 const uint16_t* Pt1_lo, float* partial_a, float* dA, const uint16_t* dY, int64_t lddy,
+                                 int64_t c_out, const uint16_t* Pt2_hi, const uint16_t* Pt2_lo, float* partial_b,
+                                 float* dB, int64_t t, int32_t r, hipStream_t stream) {
     ProfScope prof(K_LORA_GRAD, stream);
     const int64_t t_pad = (t + 31) / 32 * 32;
-    int nslab, rows;
-    lora_grad_plan(t, c, &nslab, &rows);
-    dim3 grid((unsigned)((c + kGradCols - 1) / kGradCols), (unsigned)nslab);
-#define QUAFF_GRAD(N)                                                                                                \
-    case N:                                                                                                          \
-        hipLaunchKernelGGL((lora_grad_kernel<N>), grid, dim3(256), 0, stream, Q, ldq, t, (int)c, Pt_hi, Pt_lo, t_pad, \
-                           rows, partial);                                                                           \
+    GradPair pair;
+    auto fill = [&](GradProblem& p, const uint16_t* Q, int64_t ldq, int64_t c, const uint16_t* hi, const uint16_t* lo,
+                    float* partial, float* out, int transposed) {
+        p.Q = Q; p.ldq = ldq; p.c = (int)c; p.Pt_hi = hi; p.Pt_lo = lo;
+        lora_grad_plan(t, c, &p.nslab, &p.rows_per_slab);
+        p.chunks = (int)((c + kGradCols - 1) / kGradCols);
+        p.partial = partial; p.out = out; p.transposed = transposed;
+    };
+    fill(pair.p[0], X, ldx, c_in, Pt1_hi, Pt1_lo, partial_a, dA, 1);
+    fill(pair.p[1], dY, lddy, c_out, Pt2_hi, Pt2_lo, partial_b, dB, 0);
+    const int gx = pair.p[0].chunks > pair.p[1].chunks ? pair.p[0].chunks : pair.p[1].chunks;
+    const int gy = pair.p[0].nslab > pair.p[1].nslab ? pair.p[0].nslab : pair.p[1].nslab;
+    dim3 grid((unsigned)gx, (unsigned)gy, 2);
+#define QUAFF_GRAD(N)                                                                              \
+    case N:                                                                                        \
+        hipLaunchKernelGGL((lora_grad_kernel<N>), grid, dim3(256), 0, stream, pair, t, t_pad);     \
         break;
     switch (r / 16) {
         QUAFF_GRAD(1) QUAFF_GRAD(2) QUAFF_GRAD(3) QUAFF_GRAD(4)
@@ -197,10 +228,10 @@ hipError_t launch_lora_grad(const uint16_t* Q, int64_t ldq, int64_t t, int64_t c
 #undef QUAFF_GRAD
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    int64_t blocks = ((int64_t)r * c + 255) / 256;
-    if (blocks > 2048) blocks = 2048;
-    hipLaunchKernelGGL(lora_grad_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, partial, nslab, (int)r,
-                       (int)c, out, transposed ? 1 : 0);
+    const int64_t cmax = c_in > c_out ? c_in : c_out;
+    int64_t blocks = ((int64_t)r * cmax + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(lora_grad_reduce_kernel, dim3((unsigned)blocks, 2), dim3(256), 0, stream, pair, (int)r);
     return hipGetLastError();
 }
 
