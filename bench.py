@@ -91,12 +91,13 @@ def main():
         L["bwd_ops"] = 2.0 * p.t * p.c_out * p.c_in if p.backward else 0.0
         layers.append(L)
 
-    def step(i):
+    def step(i, separate=None):
+        separate = args.separate_calls if separate is None else separate
         b = i % args.batches
         for L in layers:
             p, n, r = L["p"], L["n"], L["r"]
             X = L["X"][b]
-            if args.separate_calls:
+            if separate:
                 q.scale_update(X, L["O"], L["W_O"], L["wmax"], p.c_out, p.gamma, L["s"], L["cs"], L["what"], L["dwh"],
                                None, L["ws"])
                 q.quant_act(X, L["cs"], L["O"], L["Xq"], L["dx"], L["xo"] if n else None)
@@ -185,52 +186,79 @@ def main():
         for ln in open(prof_file):
             if ln.strip().startswith("gemm_traffic_bytes_per_launch"):
                 gemm_traffic = int(ln.split("=")[1])
-    # HBM-bound kernels: algorithmic bytes / measured time
-    # forward quantizer: 2 B read + 1 B written per element; backward: one launch quantizes dY and forms dY B^T
-    quant_bytes = fused_bytes = lora_bytes = 0.0
-    for L in layers:
-        p, r = L["p"], L["r"]
-        quant_bytes += 3.0 * p.t * p.c_in + 4.0 * p.t + p.t * L["n_pad"]
-        if r:
-            lora_bytes += 2.0 * p.t * p.c_in + 2.0 * p.c_in * r + 8.0 * p.t * r + 4.0 * p.c_out * r
-        if p.backward:
-            fused_bytes += 3.0 * p.t * p.c_out + 4.0 * p.t + (2.0 * p.c_out * r + 8.0 * p.t * r if r else 0.0)
-    kernels = {name: {"avg_us": round(v[0] / v[1] * 1e3, 2), "launches_per_step": v[1] // prof_steps,
-                      "us_per_step": round(v[0] / prof_steps * 1e3, 2)} for name, v in kinds.items()}
-
-    def hbm(name, nbytes):
-        if name in kernels and nbytes:
-            ms = kinds[name][0] / prof_steps
-            kernels[name]["achieved_GBs"] = round(nbytes / (ms * 1e-3) / 1e9, 1)
-            kernels[name]["frac_hbm_peak"] = round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
-    if "quant_rows+lora_down" in kernels:
-        hbm("quant_rows", quant_bytes)
-        hbm("quant_rows+lora_down", fused_bytes)
-        hbm("lora_down", lora_bytes)
-        hbm("colmax_outlier+lora_down", lora_bytes)   # the abs-max gather adds about a third of X's bytes
-    else:   # rank 0 or shapes the combined launch does not cover: separate launches in the backward pass too
-        hbm("quant_rows", quant_bytes + fused_bytes)
-        hbm("lora_down", lora_bytes)
-    # column abs-max: useful bytes are the 2-byte outlier entries; what the memory system must fetch is one
-    # 64-byte segment per (row, distinct segment touched by O) - counted here from the outlier positions
-    for col_kind in ("colmax_outlier",):
-        if col_kind not in kernels:
-            continue
-        useful = fetched = 0.0
+    def kernel_stats(kinds, launches, prof_steps):
+        # HBM-bound kernels: algorithmic bytes / measured time
+        # forward quantizer: 2 B read + 1 B written per element; backward: one launch quantizes dY and forms dY B^T
+        quant_bytes = fused_bytes = lora_bytes = 0.0
         for L in layers:
-            if L["n"]:
-                seg = len(set(int(o) // 32 for o in L["O"].cpu().tolist()))
-                useful += 2.0 * L["p"].t * L["n"]
-                # the library streams whole rows when the outliers touch most segments anyway (n * 64 >= c_in)
-                fetched += 2.0 * L["p"].t * L["p"].c_in if L["n"] * 64 >= L["p"].c_in else 64.0 * L["p"].t * seg
-        col_ms = kinds["colmax_outlier"][0] / prof_steps
-        kernels["colmax_outlier"]["useful_GBs"] = round(useful / (col_ms * 1e-3) / 1e9, 1)
-        kernels["colmax_outlier"]["fetched_GBs"] = round(fetched / (col_ms * 1e-3) / 1e9, 1)
-        kernels["colmax_outlier"]["frac_hbm_peak_fetched"] = round(fetched / (col_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
-    for name, v in kinds.items():
-        ds = sorted(ms for nm, ms in launches if nm == name)
-        kernels[name]["min_us"] = round(ds[0] * 1e3, 2)
-        kernels[name]["median_us"] = round(ds[len(ds) // 2] * 1e3, 2)
+            p, r = L["p"], L["r"]
+            quant_bytes += 3.0 * p.t * p.c_in + 4.0 * p.t + p.t * L["n_pad"]
+            if r:
+                lora_bytes += 2.0 * p.t * p.c_in + 2.0 * p.c_in * r + 8.0 * p.t * r + 4.0 * p.c_out * r
+            if p.backward:
+                fused_bytes += 3.0 * p.t * p.c_out + 4.0 * p.t + (2.0 * p.c_out * r + 8.0 * p.t * r if r else 0.0)
+        kernels = {name: {"avg_us": round(v[0] / v[1] * 1e3, 2), "launches_per_step": v[1] // prof_steps,
+                          "us_per_step": round(v[0] / prof_steps * 1e3, 2)} for name, v in kinds.items()}
+
+        def hbm(name, nbytes):
+            if name in kernels and nbytes:
+                ms = kinds[name][0] / prof_steps
+                kernels[name]["achieved_GBs"] = round(nbytes / (ms * 1e-3) / 1e9, 1)
+                kernels[name]["frac_hbm_peak"] = round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+        if "quant_rows+lora_down" in kernels:
+            hbm("quant_rows", quant_bytes)
+            hbm("quant_rows+lora_down", fused_bytes)
+            hbm("lora_down", lora_bytes)
+            hbm("colmax_outlier+lora_down", lora_bytes)   # the abs-max gather adds about a third of X's bytes
+            what_bytes = sum(4.0 * L["n"] * L["p"].c_out + L["n_pad"] * L["p"].c_out + 4.0 * L["p"].c_out for L in layers)
+            hbm("momentum_what+quant_rows", quant_bytes + what_bytes)
+        else:   # rank 0 or shapes the combined launch does not cover: separate launches in the backward pass too
+            hbm("quant_rows", quant_bytes + fused_bytes)
+            hbm("lora_down", lora_bytes)
+        # column abs-max: useful bytes are the 2-byte outlier entries; what the memory system must fetch is one
+        # 64-byte segment per (row, distinct segment touched by O) - counted here from the outlier positions
+        for col_kind in ("colmax_outlier",):
+            if col_kind not in kernels:
+                continue
+            useful = fetched = 0.0
+            for L in layers:
+                if L["n"]:
+                    seg = len(set(int(o) // 32 for o in L["O"].cpu().tolist()))
+                    useful += 2.0 * L["p"].t * L["n"]
+                    # the library streams whole rows when the outliers touch most segments anyway (n * 64 >= c_in)
+                    fetched += 2.0 * L["p"].t * L["p"].c_in if L["n"] * 64 >= L["p"].c_in else 64.0 * L["p"].t * seg
+            col_ms = kinds["colmax_outlier"][0] / prof_steps
+            kernels["colmax_outlier"]["useful_GBs"] = round(useful / (col_ms * 1e-3) / 1e9, 1)
+            kernels["colmax_outlier"]["fetched_GBs"] = round(fetched / (col_ms * 1e-3) / 1e9, 1)
+            kernels["colmax_outlier"]["frac_hbm_peak_fetched"] = round(fetched / (col_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+        for name, v in kinds.items():
+            ds = sorted(ms for nm, ms in launches if nm == name)
+            kernels[name]["min_us"] = round(ds[0] * 1e3, 2)
+            kernels[name]["median_us"] = round(ds[len(ds) // 2] * 1e3, 2)
+        return kernels
+
+    kernels = kernel_stats(kinds, launches, prof_steps)
+    kernels_separate = None
+    if not args.separate_calls:
+        # the same step through the four separate calls, for the stand-alone figures of the abs-max, momentum,
+        # quantizer and down-projection kernels
+        for i in range(3):              # untimed: the first launch of a kernel pays for loading its code
+            step(i, separate=True)
+        torch.cuda.synchronize()
+        q.profile_enable(True)
+        sep_steps = min(args.steps, 10)
+        for i in range(sep_steps):
+            step(i, separate=True)
+        torch.cuda.synchronize()
+        sep_launches = q.profile_launches()
+        q.profile_enable(False)
+        sep_kinds = {}
+        for name, ms in sep_launches:
+            k = sep_kinds.setdefault(name, [0.0, 0])
+            k[0] += ms
+            k[1] += 1
+        kernels_separate = kernel_stats(sep_kinds, sep_launches, sep_steps)
+        kernels_separate.pop("gemm_i8", None)
 
     out = {
         "metric": "INT8 quantized-linear TOPS fwd+bwd_dx at Phi-3 shapes; % INT8 MFMA peak",
@@ -259,6 +287,7 @@ def main():
                      "WRITE_SIZE, scaled by the copy kernel; profiles/gemm_i8_hbm_traffic_phi3_attention.md)",
                      "algorithmic_bytes_per_launch": round(gemm_bytes / len(order)), "per_shape": gemm_shapes},
         "kernels": kernels,
+        "kernels_with_separate_calls": kernels_separate,
     }
 
     # ---- rows beyond the headline metric, timed on their own (not part of `value`)
