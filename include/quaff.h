@@ -60,8 +60,11 @@ int quaff_last_hip_error(void);
 /* n_p: n_outlier rounded up to the INT8 MFMA contraction step (64). */
 int32_t quaff_padded_outliers(int32_t n_outlier);
 
-/* Bytes of the opaque packed INT8 weight produced by quaff_prepare_weight.  The packing stores the codes
- * contraction-contiguous for both products of the layer (over c_in for Y, over c_out for dX). */
+/* Bytes of the opaque packed INT8 weight produced by quaff_prepare_weight: one byte per weight (c_in rounded up to a
+ * multiple of 64, c_out to a multiple of 2).  The one copy serves both products of the layer: element (j, k) of the
+ * [c_out x c_in] code matrix sits at byte (j / 2) * 2 * cpad + (k / 64) * 128 + (j % 2) * 64 + k % 64, so that every
+ * 128-byte line holds 64 consecutive input channels of two neighbouring output channels; the forward product reads
+ * it contraction-contiguous, the input-gradient product transposes 8 x 8 byte blocks while reading them from LDS. */
 size_t quaff_packed_weight_bytes(int64_t c_in, int64_t c_out);
 
 /* Bytes of scratch that the per-step calls below need for the given problem (the maximum over the calls). */

@@ -23,13 +23,11 @@ bool dims_ok(int64_t t, int64_t c_in, int64_t c_out) {
 }
 bool rank_ok(int32_t r) { return r == 0 || (r > 0 && r <= 64 && r % 16 == 0); }
 
-struct PackedWeight {
-    int8_t* Wt;   // [c_out x c_in]
-    int8_t* Wn;   // [c_in x c_out]
-};
-PackedWeight unpack(const void* packed, int64_t c_in, int64_t c_out) {
-    int8_t* base = const_cast<int8_t*>(static_cast<const int8_t*>(packed));
-    return {base, base + align_up((size_t)c_in * (size_t)c_out)};
+// the packed weight codes as the B operand of the forward (c_out x c_in) or of the input-gradient product
+void set_weight_operand(quaff::GemmArgs& g, const void* packed, int64_t c_in, bool gradient) {
+    g.B = static_cast<const int8_t*>(packed);
+    g.ldb = quaff::packed_weight_cpad(c_in);
+    g.b_layout = gradient ? quaff::kPackedKN : quaff::kPackedNK;
 }
 
 // workspace layouts -------------------------------------------------------------------------------
@@ -103,7 +101,7 @@ int32_t quaff_padded_outliers(int32_t n_outlier) { return n_outlier <= 0 ? 0 : p
 
 size_t quaff_packed_weight_bytes(int64_t c_in, int64_t c_out) {
     if (c_in <= 0 || c_out <= 0) return 0;
-    return 2 * align_up((size_t)c_in * (size_t)c_out);
+    return align_up(quaff::packed_weight_bytes(c_in, c_out));
 }
 
 size_t quaff_prepare_workspace_bytes(int64_t c_in, int64_t c_out) {
@@ -126,8 +124,7 @@ int quaff_prepare_weight(const float* W, int64_t c_in, int64_t c_out, int64_t ld
     if (!dims_ok(1, c_in, c_out) || n_outlier < 0 || n_outlier > c_in || ldw < c_out) return QUAFF_ERR_SHAPE;
     if (!workspace || workspace_bytes < quaff_prepare_workspace_bytes(c_in, c_out)) return QUAFF_ERR_WORKSPACE;
     if (!aligned16(W) || !aligned16(Wq_packed) || !aligned16(workspace)) return QUAFF_ERR_ALIGN;
-    PackedWeight pw = unpack(Wq_packed, c_in, c_out);
-    return hip_status(quaff::launch_prepare_weight(W, c_in, c_out, ldw, O, n_outlier, pw.Wt, pw.Wn, delta_w, W_O,
+    return hip_status(quaff::launch_prepare_weight(W, c_in, c_out, ldw, O, n_outlier, static_cast<int8_t*>(Wq_packed), delta_w, W_O,
                                                    wmax_O, Wq_plain, static_cast<float*>(workspace),
                                                    static_cast<hipStream_t>(stream)));
 }
@@ -167,9 +164,9 @@ static int fwd_common(const int8_t* Xq, const float* delta_x, const int8_t* xq_O
     if (!dims_ok(t, c_in, c_out) || n_outlier < 0 || n_outlier > c_in) return QUAFF_ERR_SHAPE;
     if (!aligned16(Xq) || !aligned16(Wq_packed) || (n_outlier > 0 && (!aligned16(xq_O) || !aligned16(what_int))))
         return QUAFF_ERR_ALIGN;
-    PackedWeight pw = unpack(Wq_packed, c_in, c_out);
     g = quaff::GemmArgs{};
-    g.A = Xq; g.lda = c_in; g.B = pw.Wt; g.ldb = c_in;
+    g.A = Xq; g.lda = c_in;
+    set_weight_operand(g, Wq_packed, c_in, false);
     g.M = t; g.N = c_out; g.K = c_in;
     g.K2 = n_outlier > 0 ? pad_outliers(n_outlier) : 0;
     g.A2 = xq_O; g.B2 = what_int;
@@ -264,9 +261,9 @@ static int linear_bwd_dx_impl(const uint16_t* dY, int64_t t, int64_t lddy, const
     char* base = static_cast<char*>(workspace);
     int8_t* gq = reinterpret_cast<int8_t*>(base + w.gq);
     float* dg = reinterpret_cast<float*>(base + w.dg);
-    PackedWeight pw = unpack(Wq_packed, c_in, c_out);
     quaff::GemmArgs g{};
-    g.A = gq; g.lda = c_out; g.B = pw.Wn; g.ldb = c_out;
+    g.A = gq; g.lda = c_out;
+    set_weight_operand(g, Wq_packed, c_in, true);
     g.M = t; g.N = c_in; g.K = c_out;
     g.row_scale = dg;
     int st;
@@ -320,11 +317,11 @@ int quaff_linear_bwd_dx_acc(const uint16_t* dY, int64_t t, int64_t lddy, const v
     if (!aligned16(dY) || !aligned16(Wq_packed) || !aligned16(delta_w) || !aligned16(Gq) || lddy % 8 != 0)
         return QUAFF_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    PackedWeight pw = unpack(Wq_packed, c_in, c_out);
     int st = hip_status(quaff::launch_quant_act(dY, t, c_out, lddy, delta_w, nullptr, 0, Gq, delta_g, nullptr, s));
     if (st != QUAFF_OK) return st;
     quaff::GemmArgs g{};
-    g.A = Gq; g.lda = c_out; g.B = pw.Wn; g.ldb = c_out;
+    g.A = Gq; g.lda = c_out;
+    set_weight_operand(g, Wq_packed, c_in, true);
     g.M = t; g.N = c_in; g.K = c_out;
     g.acc1 = acc;
     return hip_status(quaff::launch_gemm(g, true, s));

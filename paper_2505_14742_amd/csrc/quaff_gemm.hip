@@ -1,6 +1,8 @@
 // INT8 MFMA GEMM with int32 accumulation and a fused dequantising epilogue (Eq. 9 of the paper) that also
 // adds the rank-r LoRA term.  The same kernels serve the forward product (contraction over c_in) and the
-// input-gradient product (contraction over c_out): both operands arrive contraction-contiguous.
+// input-gradient product (contraction over c_out).  A is contraction-contiguous; B is either a plain
+// contraction-contiguous [N x K] matrix or the packed weight codes (one copy, quaff_internal.h), read as [N x K] by
+// the forward product and as [K x N], through transposing LDS reads, by the input-gradient product.
 //
 //   C[i, j] = row_scale[i] * ( acc1[i, j] * col_scale[j] + acc2[i, j] * col_scale2[j] ) + sum_p T[i, p] L[j, p]
 //   acc1 = A B^T   (K long, the hot loop),   acc2 = A2 B2^T   (K2 = padded outlier count, done in the epilogue)
@@ -8,8 +10,8 @@
 // Two kernels share the epilogue:
 //   gemm_i8_dma_kernel  the fast path (contraction a multiple of 64): direct-to-LDS operand streaming through a ring
 //                       of stages, v_mfma_i32_32x32x32_i8, XCD-aware tile order (quaff_gemm_dma.h);
-//   gemm_i8_kernel      register-staged fallback for contractions that are not a multiple of 64
-//                       (quaff_gemm_kernel.h).
+//   gemm_i8_kernel      register-staged fallback for contractions that are not a multiple of 64 (128 for the
+//                       [K x N] reading) (quaff_gemm_kernel.h).
 #include "quaff_gemm_dma.h"
 
 namespace quaff {
@@ -19,36 +21,32 @@ static hipError_t launch_generic(const GemmArgs& g, bool dump, hipStream_t strea
     int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (int)((g.N + BN - 1) / BN);
     size_t lds = 2 * (size_t)(BM + BN) * BK;
     dim3 grid((unsigned)(tiles_m * tiles_n));
-    if (dump) {
-        auto k = gemm_i8_kernel<BM, BN, BK, WGM, WGN, true>;
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(k, grid, dim3(64 * WGM * WGN), lds, stream, g, tiles_n);
-    } else {
-        auto k = gemm_i8_kernel<BM, BN, BK, WGM, WGN, false>;
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(k, grid, dim3(64 * WGM * WGN), lds, stream, g, tiles_n);
-    }
+    const bool bt = g.b_layout == kPackedKN;
+    auto k = dump ? (bt ? gemm_i8_kernel<BM, BN, BK, WGM, WGN, true, true> : gemm_i8_kernel<BM, BN, BK, WGM, WGN, true, false>)
+                  : (bt ? gemm_i8_kernel<BM, BN, BK, WGM, WGN, false, true> : gemm_i8_kernel<BM, BN, BK, WGM, WGN, false, false>);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k, grid, dim3(64 * WGM * WGN), lds, stream, g, tiles_n);
     return hipGetLastError();
 }
 
-template <int BM, int BN, int WGM, int WGN, int STAGES, int MINB, int PAIR = 0>
+// BT: B is read as [K x N] from the packed weight codes (wide-stage main loop only)
+template <int BM, int BN, int WGM, int WGN, int STAGES, int MINB, int PAIR = 0, bool BT = false>
 static hipError_t launch_dma(const GemmArgs& g, bool dump, hipStream_t stream) {
     using C = DmaCfg<BM, BN, WGM, WGN, STAGES>;
     int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (int)((g.N + BN - 1) / BN);
     TileMap tm = make_tile_map(tiles_m, tiles_n);
     dim3 grid((unsigned)(8 * tm.rm * tm.rn)), block(C::NT);
     if (dump) {
-        auto k = gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, true, MINB, PAIR>;
+        auto k = gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, true, MINB, PAIR, false, false, false, BT>;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, block, C::LDS_BYTES, stream, g, tm);
     } else if ((int64_t)(g.K2 / 64) * C::K2_PLANES_BYTES <= C::EPI_LIMIT) {
         // the epilogue operands are staged through the idle LDS ring
-        auto k = g.C16          ? gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, false, MINB, PAIR, true, false, true>
-                 : g.accumulate ? gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, false, MINB, PAIR, true, true>
-                                : gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, false, MINB, PAIR, true, false>;
+        auto k = g.C16          ? gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, false, MINB, PAIR, true, false, true, BT>
+                 : g.accumulate ? gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, false, MINB, PAIR, true, true, false, BT>
+                                : gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, false, MINB, PAIR, true, false, false, BT>;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_ALLOC);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(k, grid, block, C::LDS_ALLOC, stream, g, tm);
@@ -89,12 +87,21 @@ int choose_tile(int64_t M, int64_t N) {
 
 static hipError_t launch_gemm_one(const GemmArgs& g, bool dump_acc, hipStream_t stream);
 
+// the direct-to-LDS loader addresses an operand with 32-bit offsets from its tile's first row
+static bool fast_path_ok(const GemmArgs& g) {
+    const int64_t lim32 = (int64_t)1 << 32;
+    if (g.K % 64 != 0 || g.M * g.lda >= lim32) return false;
+    if (g.b_layout == kPackedKN) return g.K % 128 == 0 && 130 * g.ldb < lim32;   // 128 contraction rows per stage
+    return (g.N + 2) * g.ldb < lim32;
+}
+
+
 hipError_t launch_gemm(const GemmArgs& g, bool dump_acc, hipStream_t stream) {
     ProfScope prof(K_GEMM, stream);
     // A second product too wide for the epilogue's LDS staging (more than two to four 64-wide outlier slices,
     // depending on the tile shape) runs as a launch of its own that writes row_scale * acc2 * col_scale2, and the
     // main product then accumulates onto it: one extra write and read of the output instead of a slow epilogue.
-    const bool main_fast = g.K % 64 == 0 && g.M * g.lda < ((int64_t)1 << 32) && g.N * g.ldb < ((int64_t)1 << 32);
+    const bool main_fast = fast_path_ok(g);
     // bf16 output exists in the fast kernel's single-launch form only
     if (g.C16 && (!main_fast || g.K2 > 128 || dump_acc)) return hipErrorNotSupported;
     if (!dump_acc && g.K2 > 128 && main_fast) {
@@ -114,9 +121,15 @@ hipError_t launch_gemm(const GemmArgs& g, bool dump_acc, hipStream_t stream) {
 }
 
 hipError_t launch_gemm_one(const GemmArgs& g, bool dump_acc, hipStream_t stream) {
-    const int64_t lim32 = (int64_t)1 << 32;
-    const bool dma_ok = g.K % 64 == 0 && g.M * g.lda < lim32 && g.N * g.ldb < lim32;
-    if (!dma_ok) return launch_generic<128, 128, 64, 2, 2>(g, dump_acc, stream);
+    if (!fast_path_ok(g)) return launch_generic<128, 128, 64, 2, 2>(g, dump_acc, stream);
+    if (g.b_layout == kPackedKN) {
+        switch (choose_tile(g.M, g.N)) {
+            case 0: return launch_dma<256, 256, 2, 4, 4, 1, 2, true>(g, dump_acc, stream);
+            case 1: return launch_dma<256, 288, 4, 3, 4, 1, 2, true>(g, dump_acc, stream);
+            case 2: return launch_dma<256, 128, 4, 2, 4, 1, 2, true>(g, dump_acc, stream);
+            default: return launch_dma<128, 192, 2, 2, 4, 2, 2, true>(g, dump_acc, stream);
+        }
+    }
     // contractions that are a multiple of 128 run the wide-stage main loop (128-byte row segments per direct load)
     const bool wide = g.K % 128 == 0;
     switch (choose_tile(g.M, g.N)) {

@@ -16,6 +16,42 @@ typedef __attribute__((address_space(3))) float lds_f32;
 // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt = [3:0] and [15:14])
 #define QUAFF_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 
+// B operand read as [K x N] from the packed weight codes (N = c_in contiguous within a 16-byte chunk) instead of
+// contraction-contiguous.  A stage then holds 128 contraction rows x BN columns, and the MFMA fragment (16
+// contraction bytes of one column per lane) is gathered with the transposing LDS read ds_read_b64_tr_b8: in every
+// group of 16 lanes, lane i receives byte (i & 7) of the 8-byte pieces addressed by lanes 2 j + (i >> 3), j = 0..7.
+// Lane 2 j + p of a group therefore addresses contraction row j, column piece p, and two such reads give a lane its
+// 16 contraction bytes.  A read touches 8 rows x 32 bytes; the layouts below put these in different banks.
+//   BN a multiple of 64: column-group major, [BN / 64][128 rows][64 bytes].  A direct load (1 KiB) then fills 16 rows
+//     of one 64-column group, which are 8 whole 128-byte lines of the packed codes.  The two 32-byte halves of a row
+//     swap places in rows 4..7 of every 8.
+//   otherwise (288): row major, [128 rows][BN bytes], no swizzle needed (288 = 32 mod 256).
+template <int BN>
+struct BtStage {
+    static constexpr bool GROUPED = BN % 64 == 0;
+    static constexpr int ROW_STRIDE = GROUPED ? 64 : BN;
+    static_assert(GROUPED || BN % 256 == 32, "row-major stage rows must rotate through the banks by themselves");
+    // which (contraction row, first column) the 16-byte LDS slot number `slot` of the stage's B part holds
+    __device__ static __forceinline__ void slot_source(int slot, int& krow, int& col) {
+        if (GROUPED) {
+            const int cg = slot >> 9, ch = slot & 3;
+            krow = (slot >> 2) & 127;
+            col = cg * 64 + (((ch >> 1) ^ ((krow >> 2) & 1)) * 32) + (ch & 1) * 16;
+        } else {
+            krow = slot / (BN / 16);
+            col = (slot % (BN / 16)) * 16;
+        }
+    }
+    // byte offset, inside the B part, of the 8-byte piece a lane addresses for the 32-column block number c32:
+    // lane = 16 grp + 2 jj + piece; contraction row (grp >> 1) * 16 + jj of the 32-row sub-step, + 8 for the second read
+    __device__ static __forceinline__ int piece_offset(int lane, int c32) {
+        const int grp = lane >> 4, jj = (lane & 15) >> 1, piece = lane & 1;
+        const int krow = (grp >> 1) * 16 + jj, in32 = (grp & 1) * 16 + piece * 8;
+        if (GROUPED) return (c32 >> 1) * 8192 + krow * 64 + (((c32 & 1) ^ ((jj >> 2) & 1)) * 32) + in32;
+        return krow * BN + c32 * 32 + in32;
+    }
+};
+
 template <int BM, int BN, int WGM, int WGN, int STAGES>
 struct DmaCfg {
     static constexpr int BK = 64, BM_ = BM, BN_ = BN;
@@ -26,6 +62,7 @@ struct DmaCfg {
     static constexpr int NGROUP = (BM + BN) / 16;         // 16-row groups per stage, one direct load (1 KiB) each
     static constexpr int NLOAD = (NGROUP + NW - 1) / NW;  // direct loads per lane per stage
     static constexpr int STAGES_ = STAGES;
+    static constexpr bool WAVE_SCALAR = NW >= 8 && TM * TN <= 6;
     // wide-stage variant (gemm_mainloop_dma128): 128 contraction bytes per row, one direct load fills 8 rows
     static constexpr int WSTAGE_BYTES = (BM + BN) * 128, A_WBYTES = BM * 128;
     static constexpr int NGROUP_W = (BM + BN) / 8, NLOAD_W = (NGROUP_W + NW - 1) / NW;
@@ -63,11 +100,12 @@ template <class C>
 __device__ __forceinline__ void gemm_mainloop_dma(const int8_t* __restrict__ gA, const int8_t* __restrict__ gB,
                                                   const uint32_t (&voff)[C::NLOAD], int KT,
                                                   lds_i8* __restrict__ dma, const lds_i8* __restrict__ rd, int wave,
-                                                  int a_frag_off, int b_frag_off, i32x16 (&acc)[C::TM][C::TN]) {
+                                                  int a_frag_off, int b_frag_off, int b_step,
+                                                  i32x16 (&acc)[C::TM][C::TN]) {
     constexpr int TM = C::TM, TN = C::TN, NLOAD = C::NLOAD, STAGES = C::STAGES_;
 
     auto issue = [&](int tile, int stage) {
-        const int64_t k0 = (int64_t)tile * C::BK;
+        const int64_t k0 = (int64_t)tile * C::BK, kb = (int64_t)tile * b_step;   // b_step: bytes of B per stage
 #pragma unroll
         for (int j = 0; j < NLOAD; ++j) {
             // group q of the stage: A rows first, then B rows.  A wavefront whose last slot falls past the end repeats
@@ -75,7 +113,7 @@ __device__ __forceinline__ void gemm_mainloop_dma(const int8_t* __restrict__ gA,
             int q = j * C::NW + wave;
             if (q >= C::NGROUP) q -= C::NW;
             const bool isA = q < C::A_BYTES / 1024;
-            const int8_t* src = (isA ? gA : gB) + k0 + voff[j];
+            const int8_t* src = (isA ? gA + k0 : gB + kb) + voff[j];
             lds_i8* dst = dma + stage * C::STAGE_BYTES + q * 1024;
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                              (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
@@ -145,20 +183,24 @@ __device__ __forceinline__ void gemm_mainloop_dma(const int8_t* __restrict__ gA,
 // serves two 64-byte contraction steps.  Row r of a stage is 128 bytes, its 16-byte chunk c sits in slot
 // c ^ ((r >> 1) & 7): fragment reads (32 rows x one chunk per half wavefront) are then bank-conflict free.
 // K must be a multiple of 128.
-template <class C>
+// BT: B is read as [K x N] from the packed weight codes (see BtStage); b_off[j] is then this lane's byte offset of the
+// 8-byte piece it addresses for column block j in the first 32-row sub-step of a stage.
+template <class C, bool BT = false>
 __device__ __forceinline__ void gemm_mainloop_dma128(const int8_t* __restrict__ gA, const int8_t* __restrict__ gB,
                                                      const uint32_t (&voff)[C::NLOAD_W], int KT,
                                                      lds_i8* __restrict__ dma, const lds_i8* __restrict__ rd, int wave,
-                                                     int a_frag_off, int b_frag_off, i32x16 (&acc)[C::TM][C::TN]) {
-    constexpr int TM = C::TM, TN = C::TN, NLOAD = C::NLOAD_W;
+                                                     int a_frag_off, const int (&b_off)[C::TN], int64_t b_step,
+                                                     i32x16 (&acc)[C::TM][C::TN]) {
+    constexpr int TM = C::TM, TN = C::TN, NLOAD = C::NLOAD_W;   // b_step: bytes between consecutive stages of B
     auto issue = [&](int tile, int stage) {
-        const int64_t k0 = (int64_t)tile * 128;
+        const int8_t* const pa = gA + (int64_t)tile * 128;
+        const int8_t* const pb = gB + tile * b_step;
 #pragma unroll
         for (int j = 0; j < NLOAD; ++j) {
             int q = j * C::NW + wave;
             if (q >= C::NGROUP_W) q -= C::NW;
             const bool isA = q < C::BM_ / 8;
-            const int8_t* src = (isA ? gA : gB) + k0 + voff[j];
+            const int8_t* src = (isA ? pa : pb) + voff[j];
             lds_i8* dst = dma + stage * C::WSTAGE_BYTES + q * 1024;
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                              (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
@@ -170,7 +212,17 @@ __device__ __forceinline__ void gemm_mainloop_dma128(const int8_t* __restrict__ 
 #pragma unroll
         for (int i = 0; i < TM; ++i) fa[i] = *(const lds_i32x4*)(base + ((a_frag_off + i * 4096) ^ x));
 #pragma unroll
-        for (int j = 0; j < TN; ++j) fb[j] = *(const lds_i32x4*)(base + C::A_WBYTES + ((b_frag_off + j * 4096) ^ x));
+        for (int j = 0; j < TN; ++j) {
+            if constexpr (BT) {
+                constexpr int RS = BtStage<C::BN_>::ROW_STRIDE;
+                const lds_i8* pb = base + C::A_WBYTES + b_off[j] + ks * 32 * RS;
+                const i32x2 lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2*)pb);
+                const i32x2 hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2*)(pb + 8 * RS));
+                fb[j] = (i32x4){lo[0], lo[1], hi[0], hi[1]};
+            } else {
+                fb[j] = *(const lds_i32x4*)(base + C::A_WBYTES + ((b_off[0] + j * 4096) ^ x));
+            }
+        }
     };
     auto mfmas = [&](const i32x4 (&fa)[TM], const i32x4 (&fb)[TN]) {
 #pragma unroll
@@ -183,7 +235,8 @@ __device__ __forceinline__ void gemm_mainloop_dma128(const int8_t* __restrict__ 
     auto order_reads = [&](bool with_loads) {
 #pragma unroll
         for (int u = 0; u < TM + TN; ++u) {
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if (BT && u >= TM) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // a B fragment is two reads
+            else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             if (with_loads && u < NLOAD) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, MFMA_PER_READ, 0);
         }
@@ -462,7 +515,7 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
 }
 
 template <int BM, int BN, int WGM, int WGN, int STAGES, bool DUMP, int MINB = 1, int PAIR = 0, bool STAGED = false,
-          bool ACCUM = false, bool OUT16 = false>
+          bool ACCUM = false, bool OUT16 = false, bool BT = false>
 __global__ void __launch_bounds__(64 * WGM * WGN, MINB)
 gemm_i8_dma_kernel(const GemmArgs g, const TileMap tmap) {
     using C = DmaCfg<BM, BN, WGM, WGN, STAGES>;
@@ -472,7 +525,10 @@ gemm_i8_dma_kernel(const GemmArgs g, const TileMap tmap) {
     int tile_m, tile_n;
     if (!tile_of_block(tmap, blockIdx.x, tile_m, tile_n)) return;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    // The wavefront number is uniform; telling the compiler so moves the loader's address selects to scalar code,
+    // which is faster where several wavefronts share a SIMD and slower where one wavefront has it to itself (measured).
+    const int wave = C::WAVE_SCALAR ? __builtin_amdgcn_readfirstlane(tid >> 6) : tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
     const int l32 = lane & 31, lhi = lane >> 5;
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
@@ -494,8 +550,28 @@ gemm_i8_dma_kernel(const GemmArgs g, const TileMap tmap) {
             int64_t lim = (isA ? g.M : g.N) - 1;
             row = row < lim ? row : lim;
             voffw[j] = (uint32_t)(row * (isA ? g.lda : g.ldb) + chunk * 16);
+            if (!BT && !isA && g.b_layout == kPackedNK) voffw[j] = (uint32_t)weight_code_offset(row, chunk * 16, g.ldb);
+            if (BT && !isA) {
+                // B stored [K x N]: the stage's B part is 128 contraction rows of BN bytes; this lane fills the
+                // 16-byte slot number (q - BM / 8) * 64 + lane of it
+                int krow, lcol;
+                BtStage<BN>::slot_source((q - BM / 8) * 64 + lane, krow, lcol);
+                int64_t col = n0 + lcol;
+                col = col < g.N - 16 ? col : g.N - 16;      // clamp: columns past the edge are never stored
+                voffw[j] = (uint32_t)weight_code_offset(krow, col, g.ldb);
+            }
         }
+        const int64_t b_step = BT ? 128 * g.ldb : g.b_layout == kPackedNK ? 256 : 128;
         const int fragw = l32 * 128 + ((lhi ^ ((l32 >> 1) & 7)) * 16);
+        int b_off[C::TN];
+#pragma unroll
+        for (int j = 0; j < C::TN; ++j) {
+            if constexpr (BT) {
+                b_off[j] = BtStage<BN>::piece_offset(lane, wn * C::WN / 32 + j);
+            } else {
+                b_off[j] = wn * C::WN * 128 + fragw + j * 4096;
+            }
+        }
         i32x16 accw[C::TM][C::TN];
 #pragma unroll
         for (int i = 0; i < C::TM; ++i)
@@ -503,14 +579,15 @@ gemm_i8_dma_kernel(const GemmArgs g, const TileMap tmap) {
             for (int j = 0; j < C::TN; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) accw[i][j][v] = 0;
-        gemm_mainloop_dma128<C>(g.A, g.B, voffw, (int)(g.K / 128), lds, lds, wave, wm * C::WM * 128 + fragw,
-                                wn * C::WN * 128 + fragw, accw);
+        gemm_mainloop_dma128<C, BT>(g.A, g.B, voffw, (int)(g.K / 128), lds, lds, wave, wm * C::WM * 128 + fragw, b_off,
+                                    b_step, accw);
         if constexpr (STAGED && !DUMP)
             gemm_epilogue_staged<C, ACCUM, OUT16>(g, accw, lds, lds, m0, n0, wm, wn, wave, lane);
         else
             gemm_epilogue<C::TM, C::TN, DUMP>(g, accw, m0 + wm * C::WM, n0 + wn * C::WN, l32, lhi);
         return;
     }
+    static_assert(!BT || PAIR == 2, "the [K x N] B layout exists for the wide-stage main loop only");
     uint32_t voff[C::NLOAD];
     {
         const int r = lane >> 2, chunk = (lane & 3) ^ ((lane >> 4) & 3);
@@ -524,6 +601,7 @@ gemm_i8_dma_kernel(const GemmArgs g, const TileMap tmap) {
             int64_t lim = (isA ? g.M : g.N) - 1;
             row = row < lim ? row : lim;                        // clamp: rows past the edge are never stored
             voff[j] = (uint32_t)(row * (isA ? g.lda : g.ldb) + chunk * 16);
+            if (!isA && g.b_layout == kPackedNK) voff[j] = (uint32_t)weight_code_offset(row, chunk * 16, g.ldb);
         }
     }
     const int frag = l32 * 64 + ((lhi ^ ((l32 >> 2) & 3)) * 16);
@@ -537,7 +615,8 @@ gemm_i8_dma_kernel(const GemmArgs g, const TileMap tmap) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
-    gemm_mainloop_dma<C>(g.A, g.B, voff, (int)(g.K / C::BK), lds, lds, wave, a_frag_off, b_frag_off, acc);
+    gemm_mainloop_dma<C>(g.A, g.B, voff, (int)(g.K / C::BK), lds, lds, wave, a_frag_off, b_frag_off,
+                         g.b_layout == kPackedNK ? 128 : 64, acc);
 
     if constexpr (STAGED && !DUMP)
         gemm_epilogue_staged<C, ACCUM, OUT16>(g, acc, lds, lds, m0, n0, wm, wn, wave, lane);

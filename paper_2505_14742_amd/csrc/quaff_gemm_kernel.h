@@ -128,7 +128,12 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, i32x16 (&acc)[T
     }
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, bool DUMP>
+typedef int i32x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) i32x2 lds_i32x2;
+
+// BT: B is read as [K x N] from the packed weight codes; its tile is staged row-major [BK][BN] and the fragments are
+// gathered with transposing LDS reads (see BtStage in quaff_gemm_dma.h for the lane mapping).
+template <int BM, int BN, int BK, int WGM, int WGN, bool DUMP, bool BT = false>
 __global__ void __launch_bounds__(64 * WGM * WGN)
 gemm_i8_kernel(const GemmArgs g, int tiles_n) {
     constexpr int NT = 64 * WGM * WGN;            // threads per workgroup
@@ -173,9 +178,18 @@ gemm_i8_kernel(const GemmArgs g, int tiles_n) {
         }
 #pragma unroll
         for (int p = 0; p < B_LOADS; ++p) {
-            int64_t row = n0 + ld_row + p * ROWS_PER_PASS;
             pb[p] = (i32x4){0, 0, 0, 0};
-            if (row < g.N && k < g.K) pb[p] = *reinterpret_cast<const i32x4*>(g.B + row * g.ldb + k);
+            if constexpr (BT) {
+                const int idx = tid + p * NT;                     // 16-byte piece of the [BK][BN] tile
+                const int64_t kr = k0 + idx / (BN / 16), col = n0 + (idx % (BN / 16)) * 16;
+                if (kr < g.K && col < g.N)
+                    pb[p] = *reinterpret_cast<const i32x4*>(g.B + weight_code_offset(kr, col, g.ldb));
+            } else {
+                int64_t row = n0 + ld_row + p * ROWS_PER_PASS;
+                if (row < g.N && k < g.K)
+                    pb[p] = *reinterpret_cast<const i32x4*>(
+                        g.B + (g.b_layout == kPackedNK ? weight_code_offset(row, k, g.ldb) : row * g.ldb + k));
+            }
         }
     };
     auto stage = [&](int buf) {
@@ -183,9 +197,15 @@ gemm_i8_kernel(const GemmArgs g, int tiles_n) {
         for (int p = 0; p < A_LOADS; ++p)
             *reinterpret_cast<i32x4*>(As + buf * BM * BK + lds_chunk_offset<BK>(ld_row + p * ROWS_PER_PASS, ld_chunk)) = pa[p];
 #pragma unroll
-        for (int p = 0; p < B_LOADS; ++p)
-            *reinterpret_cast<i32x4*>(Bs + buf * BN * BK + lds_chunk_offset<BK>(ld_row + p * ROWS_PER_PASS, ld_chunk)) = pb[p];
+        for (int p = 0; p < B_LOADS; ++p) {
+            if constexpr (BT)
+                *reinterpret_cast<i32x4*>(Bs + buf * BN * BK + (tid + p * NT) * 16) = pb[p];
+            else
+                *reinterpret_cast<i32x4*>(Bs + buf * BN * BK + lds_chunk_offset<BK>(ld_row + p * ROWS_PER_PASS, ld_chunk)) = pb[p];
+        }
     };
+    // BT: this lane's 8-byte piece of the transposing read (lane = 16 grp + 2 jj + piece), first column block
+    const int bt_off = (((lane >> 4) >> 1) * 16 + ((lane & 15) >> 1)) * BN + wn * WN + ((lane >> 4) & 1) * 16 + (lane & 1) * 8;
 
     const int KT = (int)((g.K + BK - 1) / BK);
     fetch(0);
@@ -203,8 +223,16 @@ gemm_i8_kernel(const GemmArgs g, int tiles_n) {
             for (int i = 0; i < TM; ++i)
                 fa[i] = *reinterpret_cast<const i32x4*>(at + lds_chunk_offset<BK>(wm * WM + i * 32 + l32, ks * 2 + lhi));
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-                fb[j] = *reinterpret_cast<const i32x4*>(bt + lds_chunk_offset<BK>(wn * WN + j * 32 + l32, ks * 2 + lhi));
+            for (int j = 0; j < TN; ++j) {
+                if constexpr (BT) {
+                    const int8_t* pp = bt + bt_off + j * 32 + ks * 32 * BN;
+                    const i32x2 lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2*)pp);
+                    const i32x2 hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2*)(pp + 8 * BN));
+                    fb[j] = (i32x4){lo[0], lo[1], hi[0], hi[1]};
+                } else {
+                    fb[j] = *reinterpret_cast<const i32x4*>(bt + lds_chunk_offset<BK>(wn * WN + j * 32 + l32, ks * 2 + lhi));
+                }
+            }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll

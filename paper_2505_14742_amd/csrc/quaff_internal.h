@@ -51,7 +51,7 @@ private:
 
 // ---- host-side launchers (each enqueues on `stream`, returns a hipError_t) -------------------------
 hipError_t launch_prepare_weight(const float* W, int64_t c_in, int64_t c_out, int64_t ldw, const int32_t* O, int32_t n,
-                                 int8_t* Wt, int8_t* Wn, float* delta_w, float* W_O, float* wmax_O, int8_t* Wq_plain,
+                                 int8_t* Wp, float* delta_w, float* W_O, float* wmax_O, int8_t* Wq_plain,
                                  float* ws, hipStream_t stream);
 
 hipError_t launch_scale_update(const uint16_t* X, int64_t t, int64_t c_in, int64_t ldx, const int32_t* O, int32_t n,
@@ -123,10 +123,28 @@ bool launch_what_quant(const uint32_t* part, int nslab, int32_t n, const float* 
                        int8_t* what_int, float* delta_what, const uint16_t* X, int64_t t, int64_t c, int64_t ldx,
                        int8_t* Xq, float* delta, int8_t* xq_O, hipStream_t stream, hipError_t* err);
 
+// Packed weight codes: one int8 copy that serves both products.  Element (j, k) of the [c_out x c_in] code matrix
+// sits in a 128-byte line that holds 64 consecutive k of the two rows j & ~1 and j | 1: every 16-byte chunk is
+// contraction-contiguous for the forward product, and both products fetch whole lines (the input-gradient tiles are
+// 128 rows tall and a multiple of 64 columns wide).  `cpad` = c_in rounded up to a multiple of 64.
+enum BLayout { kPlain = 0, kPackedNK = 1, kPackedKN = 2 };
+__host__ __device__ inline int64_t weight_code_offset(int64_t j, int64_t k, int64_t cpad) {
+    return (j >> 1) * (2 * cpad) + (k >> 6) * 128 + (j & 1) * 64 + (k & 63);
+}
+
+inline int64_t packed_weight_cpad(int64_t c_in) { return (c_in + 63) / 64 * 64; }
+inline size_t packed_weight_bytes(int64_t c_in, int64_t c_out) {
+    return (size_t)((c_out + 1) / 2 * 2) * (size_t)packed_weight_cpad(c_in);
+}
+
 struct GemmArgs {
     // C[M x N] from A [M x K] int8 (lda) and B [N x K] int8 (ldb), both contraction-contiguous
     const int8_t* A; int64_t lda;
     const int8_t* B; int64_t ldb;
+    // Layout of B.  kPlain: [N x K] as above.  The other two read the packed weight codes (weight_code_offset):
+    // kPackedNK as [N x K] with N = c_out rows and K = c_in (the forward product), kPackedKN as [K x N] with
+    // K = c_out and N = c_in (the input-gradient product, transposing LDS reads); ldb is then c_in rounded up to 64.
+    int32_t b_layout;
     int64_t M, N, K;
     // optional second product with its own column scale: A2 [M x K2], B2 [N x K2], K2 a multiple of 64 (0 = none)
     const int8_t* A2; const int8_t* B2; int32_t K2;

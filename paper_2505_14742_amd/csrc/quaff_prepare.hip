@@ -1,5 +1,6 @@
 // Offline weight preprocessing (Sec. 3.3 of the paper, first paragraph): per-output-channel Eq. 1 on the
-// frozen W, both contraction-contiguous copies of the codes, and the retained full-precision rows W_O.
+// frozen W, the packed copy of the codes (one byte per weight, read by both products), and the retained
+// full-precision rows W_O.
 // Runs once per layer and is not on the per-step path, so it is written for clarity.
 #include "quaff_internal.h"
 
@@ -33,15 +34,14 @@ colmax_final_kernel(const float* __restrict__ part, int nslab, int64_t c_out, fl
 
 __global__ void __launch_bounds__(256)
 weight_codes_kernel(const float* __restrict__ W, int64_t c_in, int64_t c_out, int64_t ldw,
-                    const float* __restrict__ recip, int8_t* __restrict__ Wt, int8_t* __restrict__ Wn,
+                    const float* __restrict__ recip, int8_t* __restrict__ Wp, int64_t cpad,
                     int8_t* __restrict__ Wq_plain) {
     int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (j >= c_out) return;
     float c = recip[j];
     for (int64_t k = blockIdx.y; k < c_in; k += gridDim.y) {
         int8_t q = (int8_t)rtn_code(W[k * ldw + j], c);
-        Wn[k * c_out + j] = q;    // [c_in x c_out]: contraction over c_out contiguous (input-gradient product)
-        Wt[j * c_in + k] = q;     // [c_out x c_in]: contraction over c_in contiguous (forward product)
+        Wp[weight_code_offset(j, k, cpad)] = q;
         if (Wq_plain) Wq_plain[k * c_out + j] = q;
     }
 }
@@ -65,7 +65,7 @@ outlier_rows_kernel(const float* __restrict__ W, int64_t c_out, int64_t ldw, con
 }
 
 hipError_t launch_prepare_weight(const float* W, int64_t c_in, int64_t c_out, int64_t ldw, const int32_t* O, int32_t n,
-                                 int8_t* Wt, int8_t* Wn, float* delta_w, float* W_O, float* wmax_O, int8_t* Wq_plain,
+                                 int8_t* Wp, float* delta_w, float* W_O, float* wmax_O, int8_t* Wq_plain,
                                  float* ws, hipStream_t stream) {
     ProfScope prof(K_PREPARE, stream);
     int nslab = (int)((c_in + kSlab - 1) / kSlab);
@@ -75,7 +75,7 @@ hipError_t launch_prepare_weight(const float* W, int64_t c_in, int64_t c_out, in
     hipLaunchKernelGGL(colmax_partial_kernel, dim3(gx.x, nslab), dim3(256), 0, stream, W, c_in, c_out, ldw, part);   // nslab <= 65535 is checked by the caller
     hipLaunchKernelGGL(colmax_final_kernel, gx, dim3(256), 0, stream, part, nslab, c_out, delta_w, recip);
     hipLaunchKernelGGL(weight_codes_kernel, dim3(gx.x, (unsigned)(c_in < 65535 ? c_in : 65535)), dim3(256), 0, stream, W, c_in, c_out, ldw,
-                       recip, Wt, Wn, Wq_plain);
+                       recip, Wp, packed_weight_cpad(c_in), Wq_plain);
     if (n > 0)
         hipLaunchKernelGGL(outlier_rows_kernel, dim3(n), dim3(256), 0, stream, W, c_out, ldw, O, W_O, wmax_O);
     return hipGetLastError();

@@ -158,12 +158,11 @@ def check_prepare(L: Layer, R: OracleLayer):
     assert np.array_equal(host(L.Wq_plain), R.Wq), "W_int"
     if L.n:
         assert np.array_equal(host(L.W_O), R.W_O) and np.array_equal(host(L.wmax_O), R.wmax), "W_O / wmax"
-    # the packed copies are the same codes in both contraction orders
-    kn = L.c_in * L.c_out
-    packed = host(L.Wq_packed)
-    off = (kn + 255) // 256 * 256
-    assert np.array_equal(packed[:kn].reshape(L.c_out, L.c_in), R.Wq.T), "packed forward copy"
-    assert np.array_equal(packed[off:off + kn].reshape(L.c_in, L.c_out), R.Wq), "packed backward copy"
+    # the packed copy: element (j, k) of the [c_out x c_in] codes at (j // 2) * 2 * cpad + (k // 64) * 128 + (j % 2) * 64 + k % 64
+    cpad = (L.c_in + 63) // 64 * 64
+    j, k = np.meshgrid(np.arange(L.c_out), np.arange(L.c_in), indexing="ij")
+    off = (j // 2) * (2 * cpad) + (k // 64) * 128 + (j % 2) * 64 + (k % 64)
+    assert np.array_equal(host(L.Wq_packed)[off], R.Wq.T), "packed codes"
 
 
 def check_step(L: Layer, R: OracleLayer, X_u16, dY_u16, gamma, rows=None, backward=True, tag=""):

@@ -32,7 +32,8 @@ def test_status_strings_and_sizes():
         assert lib.quaff_status_string(code)
     assert q.padded_outliers(0) == 0 and q.padded_outliers(1) == 64 and q.padded_outliers(64) == 64
     assert q.padded_outliers(65) == 128
-    assert q.packed_weight_bytes(3072, 9216) >= 2 * 3072 * 9216
+    assert 3072 * 9216 <= q.packed_weight_bytes(3072, 9216) < 3072 * 9216 + 4096      # one byte per weight
+    assert q.packed_weight_bytes(80, 18) >= 128 * 18                                   # c_in rounded up to 64
     assert q.packed_weight_bytes(0, 16) == 0
     w0 = q.workspace_bytes(2048, 3072, 9216, 31, 16)
     assert w0 >= 2048 * 9216 + 2048 * 4 + 2 * 2048 * 16 * 2          # backward: codes of dY, steps, T hi/lo
