@@ -63,6 +63,13 @@ struct DmaCfg {
     static constexpr int NLOAD = (NGROUP + NW - 1) / NW;  // direct loads per lane per stage
     static constexpr int STAGES_ = STAGES;
     static constexpr bool WAVE_SCALAR = NW >= 8 && TM * TN <= 6;
+    // Issue order inside a 32-byte contraction sub-step of the wide-stage loop.  Where two or three wavefronts share
+    // a SIMD, the MFMAs go first and the LDS reads of the next sub-step follow the first half of them, so that the
+    // wait at the top of the next sub-step finds every read landed (-1..-8 % measured).  With one wavefront per SIMD
+    // (or only four MFMAs per sub-step) reads and MFMAs alternate one by one instead (bunching the reads, in any of
+    // three patterns tried, costs 5-15 % there: a wavefront reads about 5 KiB per sub-step and nothing else covers
+    // the LDS pipe while it waits).
+    static constexpr bool MFMA_FIRST = NW >= 8 && TM * TN >= 6;
     // wide-stage variant (gemm_mainloop_dma128): 128 contraction bytes per row, one direct load fills 8 rows
     static constexpr int WSTAGE_BYTES = (BM + BN) * 128, A_WBYTES = BM * 128;
     static constexpr int NGROUP_W = (BM + BN) / 8, NLOAD_W = (NGROUP_W + NW - 1) / NW;
@@ -233,6 +240,30 @@ __device__ __forceinline__ void gemm_mainloop_dma128(const int8_t* __restrict__ 
     };
     constexpr int MFMA_PER_READ = (TM * TN) / (TM + TN) > 0 ? (TM * TN) / (TM + TN) : 1;
     auto order_reads = [&](bool with_loads) {
+        if constexpr (C::MFMA_FIRST) {
+        // MFMA first: the reads of the next sub-step go out behind the first MFMAs and none is issued near the end,
+        // so the wait at the top of the next sub-step finds them landed.  Direct loads follow the reads.
+        constexpr int R = BT ? TM + 2 * TN : TM + TN, MF = TM * TN, U = MF / 2 > 0 ? MF / 2 : 1, V = MF - U;
+#pragma unroll
+        for (int u = 0; u < MF; ++u) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (u < U) {
+                const int cnt = R * (u + 1) / U - R * u / U;
+                if (cnt == 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                else if (cnt == 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                else if (cnt == 3) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+                else if (cnt == 4) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+            } else if (with_loads) {
+                const int v = u - U, cl = NLOAD * (v + 1) / V - NLOAD * v / V;
+                if (cl == 1) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                else if (cl == 2) __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+                else if (cl == 3) __builtin_amdgcn_sched_group_barrier(0x020, 3, 0);
+                else if (cl == 4) __builtin_amdgcn_sched_group_barrier(0x020, 4, 0);
+                else if (cl >= 5) __builtin_amdgcn_sched_group_barrier(0x020, 5, 0);
+            }
+        }
+        return;
+        }
 #pragma unroll
         for (int u = 0; u < TM + TN; ++u) {
             if (BT && u >= TM) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // a B fragment is two reads
@@ -267,11 +298,13 @@ __device__ __forceinline__ void gemm_mainloop_dma128(const int8_t* __restrict__ 
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
+        // (the compiler orders every LDS read of a region after the direct loads that precede it in the source)
+        if constexpr (C::MFMA_FIRST) read_frags(next, 0, fa0, fb0);
         {
             int t = kt + NS;
             issue(t < KT ? t : KT - 1, s);
         }
-        read_frags(next, 0, fa0, fb0);
+        if constexpr (!C::MFMA_FIRST) read_frags(next, 0, fa0, fb0);
         mfmas(fa1, fb1);
         order_reads(true);
         s = next;
