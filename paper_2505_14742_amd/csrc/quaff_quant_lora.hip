@@ -1,7 +1,10 @@
 // Backward-pass launch that runs the per-token quantizer of dY * delta_w and the LoRA down-projection dY B^T side by
 // side: both only read dY, neither fills the chip at a few thousand tokens, and each launch on its own costs several
-// microseconds of ramp-up and drain.  The first workgroups of the grid take the down-projection (they are the longer
-// ones), the rest quantize rows; the two roles share nothing but the launch.
+// microseconds of ramp-up and drain.  Two forms:
+//   quant_lora_kernel        the first workgroups of the grid take the down-projection (they are the longer ones),
+//                            the rest quantize rows; the two roles share nothing but the launch;
+//   quant_lora_rows8_kernel  (rank 16, rows of up to 5120 columns, at most 4096 rows) one pass over dY: the registers
+//                            that hold a row block as MFMA operands are also what the quantizer works on.
 #include "quaff_lora_body.h"
 #include "quaff_quant_body.h"
 
@@ -27,6 +30,150 @@ quant_lora_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx,
         quant_rows_body<64 * kLoraWaves, TPR, NV>(rb * QPG + m % QPG, X, t, c, ldx, cs, nullptr, 0, 0, Xq, delta,
                                                   nullptr);
     }
+}
+
+// One pass over dY for both results.  A workgroup of 16 wavefronts owns 8 rows; wavefront w holds the 32-column steps
+// of its slice of the contraction range in registers in the MFMA operand layout (lane (m, g): row m, eight columns of
+// group g; the rows 8..15 of the 16-row MFMA stay zero), so the same registers feed the down-projection and, once the
+// row maxima have been exchanged through LDS, the quantizer.  Wavefronts 0-7 and 8-15 produce the two parts of T.
+// NSTEP (even) = steps per wavefront; the host picks the smallest instantiation with 8 * 32 * NSTEP >= cp
+// (rows of up to 5120 columns).
+template <int R16, int NSTEP>
+__global__ void __launch_bounds__(64 * kLoraWaves)
+quant_lora_rows8_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx, const float* __restrict__ cs,
+                        int8_t* __restrict__ Xq, float* __restrict__ delta, const uint16_t* __restrict__ L, float scale,
+                        uint16_t* __restrict__ T_hi, uint16_t* __restrict__ T_lo) {
+    static_assert(kLoraParts == 2 && kLoraWaves == 16 && NSTEP % 2 == 0, "two parts of eight wavefronts each");
+    constexpr int r = R16 * 16;
+    constexpr int BU = R16 == 1 ? 6 : 2;           // steps whose B operands are in flight together
+    __shared__ float red[kLoraWaves][R16][32][4];
+    __shared__ float rmax[kLoraWaves][8];
+    // The eight rows of a wavefront share their column scales, so a scale vector fetched from global memory would be
+    // requested by eight lanes at once, twice per element (maximum pass, code pass): the texture path would then
+    // carry four times the traffic of dY itself.  The workgroup keeps one copy of cs in LDS instead.
+    extern __shared__ float cs_copy[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = lane & 15, g = lane >> 4;
+    const int64_t row = (int64_t)blockIdx.x * 8 + (m & 7);
+    const bool active = m < 8 && row < t;
+    const uint16_t* xrow = X + (row < t ? row : 0) * ldx;
+
+    const int part = wave >> 3;
+    const int cp = ((c + kLoraParts * 64 - 1) / (kLoraParts * 64)) * 64;
+    const int cbeg = part * cp, cend = cbeg + cp < c ? cbeg + cp : c;
+    const int kw = ((cp + 8 * 64 - 1) / (8 * 64)) * 64;
+    const int kbeg = cbeg + (wave & 7) * kw, kend = kbeg + kw < cend ? kbeg + kw : cend;
+
+    // this lane's eight columns of step u (two consecutive steps share whole 128-byte lines, as in lora_down_body)
+    auto col_of = [&](int u) { return kbeg + (u >> 1) * 64 + (u & 1) * 8 + g * 16; };
+    u32x4 xa[NSTEP];
+#pragma unroll
+    for (int u = 0; u < NSTEP; ++u) {
+        const int k = col_of(u);
+        xa[u] = (u32x4){0, 0, 0, 0};
+        if (active && k < kend) xa[u] = *reinterpret_cast<const u32x4*>(xrow + k);
+    }
+    f32x4 acc[R16];
+#pragma unroll
+    for (int b = 0; b < R16; ++b) acc[b] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u0 = 0; u0 < NSTEP; u0 += BU) {
+        u32x4 lb[BU][R16];
+#pragma unroll
+        for (int uu = 0; uu < BU; ++uu) {
+            const int k = col_of(u0 + uu), kc = k < kend ? k : c - 8;   // clamped: multiplied by a cleared x fragment
+#pragma unroll
+            for (int b = 0; b < R16; ++b)
+                if (u0 + uu < NSTEP) lb[uu][b] = *reinterpret_cast<const u32x4*>(L + (int64_t)(b * 16 + m) * c + kc);
+        }
+#pragma unroll
+        for (int uu = 0; uu < BU; ++uu)
+#pragma unroll
+            for (int b = 0; b < R16; ++b)
+                if (u0 + uu < NSTEP)
+                    acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xa[u0 + uu]),
+                                                                     __builtin_bit_cast(bf16x8, lb[uu][b]), acc[b], 0, 0, 0);
+    }
+    for (int i = threadIdx.x * 4; i < c; i += 64 * kLoraWaves * 4)     // c is a multiple of 16
+        *reinterpret_cast<f32x4*>(cs_copy + i) = *reinterpret_cast<const f32x4*>(cs + i);
+    __syncthreads();
+    const lds_float* csl = (const lds_float*)cs_copy;
+    // row maxima of dY * cs over this wavefront's slice
+    float mx = 0.0f;
+    if (active) {
+#pragma unroll
+        for (int u = 0; u < NSTEP; ++u) {
+            const int k = col_of(u);
+            if (k < kend) {
+                float v[8];
+                widen_scale(xa[u], csl, k, v);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) mx = fmaxf(mx, fabsf(v[e]));
+            }
+        }
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    if (lane < 8) rmax[wave][lane] = mx;
+    // element v of lane (m, g) of the MFMA result is T[4 g + v][16 b + m]: rows 0..7 live in the lane groups g < 2
+    if (g < 2)
+#pragma unroll
+        for (int b = 0; b < R16; ++b)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) red[wave][b][lane][v] = acc[b][v];
+    __syncthreads();
+
+    if (active) {
+        float mrow = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kLoraWaves; ++w) mrow = fmaxf(mrow, rmax[w][m]);
+        float d, cc;
+        rtn_steps(mrow, d, cc);
+        if (wave == 0 && g == 0) delta[row] = d;
+        int8_t* qrow = Xq + row * (int64_t)c;
+#pragma unroll
+        for (int u = 0; u < NSTEP; ++u) {
+            const int k = col_of(u);
+            if (k < kend) {
+                float v[8];
+                widen_scale(xa[u], csl, k, v);
+                *reinterpret_cast<u32x2*>(qrow + k) = pack_codes(v, cc);
+            }
+        }
+    }
+    // fixed-order sums over the eight wavefronts of each part
+    for (int e = threadIdx.x; e < kLoraParts * R16 * 32 * 4; e += 64 * kLoraWaves) {
+        const int v = e & 3, ln = (e >> 2) & 31, b = (e >> 7) % R16, p = e / (R16 * 128);
+        float sum = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 8; ++w) sum += red[p * 8 + w][b][ln][v];
+        sum = sum * scale;
+        const int64_t orow = (int64_t)blockIdx.x * 8 + (ln >> 4) * 4 + v;
+        if (orow < t) {
+            const uint32_t hi = f32_to_bf16_rne(sum);
+            const float rest = sum - __uint_as_float(hi << 16);
+            const int64_t o = (int64_t)p * t * r + orow * r + b * 16 + (ln & 15);
+            T_hi[o] = (uint16_t)hi;
+            T_lo[o] = (uint16_t)f32_to_bf16_rne(rest);
+        }
+    }
+}
+
+template <int R16>
+static bool launch_rows8(const uint16_t* X, int64_t t, int c, int64_t ldx, const float* cs, int8_t* Xq, float* delta,
+                         const uint16_t* L, float scale, uint16_t* T_hi, uint16_t* T_lo, hipStream_t stream) {
+    const int cp = ((c + kLoraParts * 64 - 1) / (kLoraParts * 64)) * 64;
+    const int nstep = ((cp + 8 * 64 - 1) / (8 * 64)) * 2;    // 32-column steps per wavefront
+    const dim3 grid((unsigned)((t + 7) / 8)), block(64 * kLoraWaves);
+#define QUAFF_R8(NS)                                                                                                  \
+    hipLaunchKernelGGL((quant_lora_rows8_kernel<R16, NS>), grid, block, (size_t)c * 4, stream, X, t, c, ldx, cs, Xq, delta, L,   \
+                       scale, T_hi, T_lo)
+    // longer slices (18 steps = 9216 columns were tried: 124 registers, 31 us against 26 us) stay with the two-role launch
+    if (nstep <= 6) QUAFF_R8(6);
+    else if (nstep <= 10) QUAFF_R8(10);
+    else return false;
+#undef QUAFF_R8
+    return true;
 }
 
 template <int R16>
@@ -60,6 +207,13 @@ bool launch_quant_lora(const uint16_t* X, int64_t t, int64_t c, int64_t ldx, con
     if (r < 16 || r > 64 || r % 16 != 0 || c > 256 * 8 * 8) return false;
     ProfScope prof(K_QUANT_LORA, stream);
     bool ok = false;
+    // One pass over dY with eight rows per workgroup where it pays: every workgroup reads all of L, so only the
+    // smallest rank (r = 64 measured: 59 us against 43 us at 4096 x 4096), rows short enough for the registers, and
+    // few enough rows that the two-role launch cannot fill the chip (at 16384 rows it is 4 % faster than this one).
+    if (r == 16 && cs != nullptr && t <= 4096) {
+        ok = launch_rows8<1>(X, t, (int)c, ldx, cs, Xq, delta, L_r_by_c, scale, T_hi, T_lo, stream);
+        if (ok) { *err = hipGetLastError(); return true; }
+    }
     switch (r / 16) {
         case 1: ok = launch_r<1>(X, t, (int)c, ldx, cs, Xq, delta, L_r_by_c, scale, T_hi, T_lo, stream); break;
         case 2: ok = launch_r<2>(X, t, (int)c, ldx, cs, Xq, delta, L_r_by_c, scale, T_hi, T_lo, stream); break;
