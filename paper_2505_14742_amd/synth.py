@@ -290,6 +290,7 @@ EDGE_CASES = [
     EdgeCase("ragged_rows", 2048 + 3, 512, 528, [1, 2, 3, 500], 16),
     EdgeCase("single_row", 1, 256, 256, [9], 16),
     EdgeCase("channels_not_multiples_of_64", 70, 208, 144, [0, 100, 207], 16),
+    EdgeCase("ragged_in_channels_fast_gradient_product", 300, 208, 256, [3, 100], 16),
     # shapes that reach every output-tile shape of the GEMM with short contractions (cheap on the CPU), crossed
     # with outlier counts of one to four 64-wide slices and LoRA ranks of one or two 32-column slices
     EdgeCase("wide_out_n65_r64", 2048, 256, 9216, list(range(1, 256, 3))[:65], 64),
