@@ -76,6 +76,10 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError("libquaff.so is not built: run `python -m paper_2505_14742_amd.build` "
                                "(there is no CPU or PyTorch fallback for this path)")
+        # PyTorch ships its own copy of the HIP runtime.  The tensors handed to this library live in that runtime's
+        # context, so it must be the one libquaff.so binds to: load torch first (a process that loaded libquaff.so
+        # before torch got two runtimes and "no device" from the first launch).
+        import torch  # noqa: F401
         l = C.CDLL(LIB_PATH)
         for name, (res, args) in SIGNATURES.items():
             fn = getattr(l, name)
