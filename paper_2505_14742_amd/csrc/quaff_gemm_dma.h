@@ -1,7 +1,10 @@
 // INT8 MFMA GEMM main kernel: operand tiles stream global -> LDS with direct-to-LDS loads (no register staging)
-// through a ring of STAGES buffers, fragments are double-buffered in registers, and one barrier per 64-byte
-// contraction step sits in the middle of the step so that the MFMAs of one half cover the LDS latency of the other.
-// See quaff_gemm.hip for the computation; the epilogue is shared with the generic kernel.
+// through a ring of buffers and fragments are double-buffered in registers.  Two main loops: 64-byte stages (one
+// barrier per 64-byte contraction step, in the middle of the step so that the MFMAs of one half cover the LDS latency
+// of the other) and, for contractions that are a multiple of 128, wide stages of 128 contraction bytes per row (one
+// barrier per two steps, whole cache lines per direct load); the wide loop also reads the B operand as [K x N] from
+// the packed weight codes for the input-gradient product.  The epilogue stages its operands through the idle ring.
+// See quaff_gemm.hip for the computation.
 #pragma once
 #include "quaff_gemm_kernel.h"
 
