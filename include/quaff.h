@@ -67,6 +67,10 @@ int32_t quaff_padded_outliers(int32_t n_outlier);
  * it contraction-contiguous, the input-gradient product transposes 8 x 8 byte blocks while reading them from LDS. */
 size_t quaff_packed_weight_bytes(int64_t c_in, int64_t c_out);
 
+/* Byte offset inside the packed weight of the code of W[k, j] (input channel k, output channel j), for tools that want
+ * to read single codes back; -1 for indices outside [0, c_in) x [0, c_out). */
+int64_t quaff_packed_weight_offset(int64_t c_in, int64_t c_out, int64_t k, int64_t j);
+
 /* Bytes of scratch that the per-step calls below need for the given problem (the maximum over the calls). */
 size_t quaff_workspace_bytes(int64_t t, int64_t c_in, int64_t c_out, int32_t n_outlier, int32_t lora_rank);
 

@@ -21,6 +21,7 @@ SIGNATURES = {
     "quaff_last_hip_error": (C.c_int, []),
     "quaff_padded_outliers": (_i32, [_i32]),
     "quaff_packed_weight_bytes": (_sz, [_i64, _i64]),
+    "quaff_packed_weight_offset": (_i64, [_i64, _i64, _i64, _i64]),
     "quaff_prepare_workspace_bytes": (_sz, [_i64, _i64]),
     "quaff_workspace_bytes": (_sz, [_i64, _i64, _i64, _i32, _i32]),
     "quaff_prepare_weight": (C.c_int, [_vp, _i64, _i64, _i64, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -108,6 +109,10 @@ def padded_outliers(n: int) -> int:
 
 def packed_weight_bytes(c_in: int, c_out: int) -> int:
     return int(lib().quaff_packed_weight_bytes(c_in, c_out))
+
+
+def packed_weight_offset(c_in: int, c_out: int, k: int, j: int) -> int:
+    return int(lib().quaff_packed_weight_offset(c_in, c_out, k, j))
 
 
 def prepare_workspace_bytes(c_in: int, c_out: int) -> int:

@@ -104,6 +104,11 @@ size_t quaff_packed_weight_bytes(int64_t c_in, int64_t c_out) {
     return align_up(quaff::packed_weight_bytes(c_in, c_out));
 }
 
+int64_t quaff_packed_weight_offset(int64_t c_in, int64_t c_out, int64_t k, int64_t j) {
+    if (c_in <= 0 || c_out <= 0 || k < 0 || k >= c_in || j < 0 || j >= c_out) return -1;
+    return quaff::weight_code_offset(j, k, quaff::packed_weight_cpad(c_in));
+}
+
 size_t quaff_prepare_workspace_bytes(int64_t c_in, int64_t c_out) {
     if (c_in <= 0 || c_out <= 0) return 0;
     return align_up(((size_t)((c_in + 63) / 64) + 1) * (size_t)c_out * sizeof(float));

@@ -44,6 +44,25 @@ def test_status_strings_and_sizes():
 A16 = 0x1000    # a non-null, 16-byte aligned fake device address: argument checks come before any device access
 
 
+def test_packed_weight_layout_is_a_bijection_with_whole_lines():
+    """Every code has its own byte inside the packed weight, and a 128-byte line holds 64 consecutive input channels
+    of two neighbouring output channels (what both products' direct loads rely on)."""
+    for c_in, c_out in ((128, 64), (208, 18), (64, 2)):
+        size = q.packed_weight_bytes(c_in, c_out)
+        seen = {}
+        for j in range(c_out):
+            for k in range(c_in):
+                off = q.packed_weight_offset(c_in, c_out, k, j)
+                assert 0 <= off < size and off not in seen
+                seen[off] = (j, k)
+        for off, (j, k) in seen.items():
+            line = off // 128
+            assert line == q.packed_weight_offset(c_in, c_out, k - k % 64, j - j % 2) // 128
+            if k % 16 < 15:                                   # 16-byte chunks are contraction-contiguous
+                assert q.packed_weight_offset(c_in, c_out, k + 1, j) == off + 1
+        assert q.packed_weight_offset(c_in, c_out, c_in, 0) == -1 and q.packed_weight_offset(c_in, c_out, 0, -1) == -1
+
+
 def test_argument_errors_are_reported_without_touching_the_device():
     lib = q.lib()
     # NULL pointers
