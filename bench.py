@@ -319,6 +319,35 @@ def main():
             "algorithmic_GBs": round(g_bytes / (g_ms * 1e-3) / 1e9, 1),
             "frac_hbm_peak": round(g_bytes / (g_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "algorithmic_bytes": "X and dY read once (2 t (c_in + c_out)); the implementation reads each twice"}
+        # the whole fine-tuning step of the layers: one forward call and one backward call (dX, dA, dB) per projection
+        for L in layers:
+            p = L["p"]
+            L["bws"] = torch.empty(q.bwd_step_workspace_bytes(p.t, p.c_in, p.c_out, L["r"]), dtype=i8, device=dev)
+
+        def two_call_step(i):
+            b = i % args.batches
+            for L in layers:
+                p, n, r = L["p"], L["n"], L["r"]
+                q.linear_fwd_step(L["X"][b], L["O"], L["W_O"] if n else None, L["wmax"] if n else None, p.c_out,
+                                  p.gamma, L["s"], L["cs"], L["what"], L["dwh"], None, L["Xq"], L["dx"],
+                                  L["xo"] if n else None, L["Wq"], L["dw"], L["A"], L["B"], r, p.lora_scale, L["Y"][b],
+                                  L["ws"])
+                q.linear_bwd_step(L["dY"][b], L["X"][b], L["Wq"], L["dw"], p.c_in, p.c_out, L["A"], L["B"], r,
+                                  p.lora_scale, L["dX"][b], L["dA"], L["dB"], L["bws"])
+        for i in range(3):
+            two_call_step(i)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(args.steps):
+            two_call_step(i)
+        e1.record()
+        torch.cuda.synchronize()
+        f_ms = e0.elapsed_time(e1) / args.steps
+        extra["full_step_with_lora_grads"] = {
+            "ms_per_step": round(f_ms, 5),
+            "calls_per_step": "quaff_linear_fwd_step + quaff_linear_bwd_step (dX, dA, dB) per projection",
+            "tops": round(total_ops / (f_ms * 1e-3) / 1e12, 2),
+            "through_separate_calls_ms": round(ms_per_step + g_ms, 5)}
     if all(L["n"] for L in layers) and all(L["p"].backward for L in layers):
         for L in layers:
             L["ows"] = torch.empty(q.bwd_dx_outlier_workspace_bytes(L["p"].t, L["p"].c_out), dtype=i8, device=dev)

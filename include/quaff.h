@@ -222,6 +222,18 @@ int quaff_lora_bwd_weights(const uint16_t* X, int64_t ldx, const uint16_t* dY, i
                            void* stream);
 
 /*
+ * One call for the backward step of a layer: quaff_linear_bwd_dx followed by quaff_lora_bwd_weights, with the
+ * down-projection dY B^T computed once for both (same arguments, same results up to the rounding of the fp32 sums of
+ * that down-projection, whose order may differ between the launches).  Needs lora_rank > 0.
+ * `workspace` must hold quaff_bwd_step_workspace_bytes(t, c_in, c_out, lora_rank) bytes.
+ */
+size_t quaff_bwd_step_workspace_bytes(int64_t t, int64_t c_in, int64_t c_out, int32_t lora_rank);
+int quaff_linear_bwd_step(const uint16_t* dY, int64_t t, int64_t lddy, const uint16_t* X, int64_t ldx,
+                          const void* Wq_packed, const float* delta_w, int64_t c_in, int64_t c_out,
+                          const uint16_t* lora_A, const uint16_t* lora_B, int32_t lora_rank, float lora_scale, float* dX,
+                          int64_t lddx, float* dA, float* dB, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Variant of the input gradient on the outlier channels (to be called after quaff_linear_bwd_dx on the same dY and
  * dX).  The paper retains the outlier rows W_O of the frozen weight in full precision (Sec. 3.3) and s cancels in
  * the true gradient (Eq. 3); this call overwrites the O columns of dX, where the quantization error of the

@@ -39,6 +39,9 @@ SIGNATURES = {
                                       _sz, _vp]),
     "quaff_linear_bwd_dx_acc": (C.c_int, [_vp, _i64, _i64, _vp, _vp, _i64, _i64, _vp, _vp, _vp, _vp]),
     "quaff_lora_bwd_workspace_bytes": (_sz, [_i64, _i64, _i64, _i32]),
+    "quaff_bwd_step_workspace_bytes": (_sz, [_i64, _i64, _i64, _i32]),
+    "quaff_linear_bwd_step": (C.c_int, [_vp, _i64, _i64, _vp, _i64, _vp, _vp, _i64, _i64, _vp, _vp, _i32, _f32, _vp,
+                                        _i64, _vp, _vp, _vp, _sz, _vp]),
     "quaff_lora_bwd_weights": (C.c_int, [_vp, _i64, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _i32, _f32, _vp, _vp, _vp,
                                          _sz, _vp]),
     "quaff_bwd_dx_outlier_workspace_bytes": (_sz, [_i64, _i64]),
@@ -187,6 +190,19 @@ def lora_bwd_weights(X, dY, lora_A, lora_B, lora_rank, lora_scale, dA, dB, works
                                         _ptr(workspace),
                                         0 if workspace is None else workspace.numel() * workspace.element_size(),
                                         _stream()))
+
+
+def bwd_step_workspace_bytes(t, c_in, c_out, lora_rank) -> int:
+    return int(lib().quaff_bwd_step_workspace_bytes(t, c_in, c_out, lora_rank))
+
+
+def linear_bwd_step(dY, X, Wq_packed, delta_w, c_in, c_out, lora_A, lora_B, lora_rank, lora_scale, dX, dA, dB, workspace):
+    t = dY.shape[0]
+    _check(lib().quaff_linear_bwd_step(_ptr(dY), t, dY.stride(0), _ptr(X), X.stride(0), _ptr(Wq_packed), _ptr(delta_w),
+                                       c_in, c_out, _ptr(lora_A), _ptr(lora_B), lora_rank, float(lora_scale), _ptr(dX),
+                                       dX.stride(0), _ptr(dA), _ptr(dB), _ptr(workspace),
+                                       0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                       _stream()))
 
 
 def bwd_dx_outlier_workspace_bytes(t, c_out) -> int:

@@ -369,6 +369,44 @@ int quaff_lora_bwd_weights(const uint16_t* X, int64_t ldx, const uint16_t* dY, i
                                                    reinterpret_cast<float*>(base + w.part_b), dB, t, lora_rank, s));
 }
 
+size_t quaff_bwd_step_workspace_bytes(int64_t t, int64_t c_in, int64_t c_out, int32_t lora_rank) {
+    if (t <= 0 || c_in <= 0 || c_out <= 0 || lora_rank <= 0) return 0;
+    return ws_bwd(t, c_out, lora_rank).total + ws_grad(t, c_in, c_out, lora_rank).total + 256;
+}
+
+int quaff_linear_bwd_step(const uint16_t* dY, int64_t t, int64_t lddy, const uint16_t* X, int64_t ldx,
+                          const void* Wq_packed, const float* delta_w, int64_t c_in, int64_t c_out,
+                          const uint16_t* lora_A, const uint16_t* lora_B, int32_t lora_rank, float lora_scale, float* dX,
+                          int64_t lddx, float* dA, float* dB, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!X || !dA || !dB) return QUAFF_ERR_NULL;
+    if (!rank_ok(lora_rank) || lora_rank == 0 || t <= 0 || c_in <= 0 || c_out <= 0 || ldx < c_in) return QUAFF_ERR_SHAPE;
+    const BwdWs wb = ws_bwd(t, c_out, lora_rank);
+    const GradWs w = ws_grad(t, c_in, c_out, lora_rank);
+    if (!workspace || workspace_bytes < wb.total + w.total) return QUAFF_ERR_WORKSPACE;
+    if (!aligned16(X) || !aligned16(workspace) || ldx % 8 != 0) return QUAFF_ERR_ALIGN;
+    // dX first: it leaves T1 = scale dY B^T (hi / lo parts of the down-projection) in its part of the workspace
+    int st = linear_bwd_dx_impl(dY, t, lddy, Wq_packed, delta_w, c_in, c_out, lora_A, lora_B, lora_rank, lora_scale, dX,
+                                nullptr, lddx, workspace, wb.total, stream);
+    if (st != QUAFF_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* bwd = static_cast<char*>(workspace);
+    char* base = bwd + wb.total;
+    auto u16 = [&](size_t off) { return reinterpret_cast<uint16_t*>(base + off); };
+    uint16_t* t1_hi = reinterpret_cast<uint16_t*>(bwd + wb.t_hi);
+    uint16_t* t1_lo = reinterpret_cast<uint16_t*>(bwd + wb.t_lo);
+    // T2 = scale X A, then the two products of quaff_lora_bwd_weights
+    st = hip_status(quaff::launch_lora_down(X, t, c_in, ldx, lora_A, false, lora_rank, lora_scale, u16(w.t2_hi),
+                                            u16(w.t2_lo), nullptr, nullptr, 0, 0, s, u16(w.at)));
+    if (st != QUAFF_OK) return st;
+    st = hip_status(quaff::launch_lora_grad_prep(t1_hi, t1_lo, u16(w.p1_hi), u16(w.p1_lo), u16(w.t2_hi), u16(w.t2_lo),
+                                                 u16(w.p2_hi), u16(w.p2_lo), t, lora_rank, s));
+    if (st != QUAFF_OK) return st;
+    return hip_status(quaff::launch_lora_grad_pair(X, ldx, c_in, u16(w.p1_hi), u16(w.p1_lo),
+                                                   reinterpret_cast<float*>(base + w.part_a), dA, dY, lddy, c_out,
+                                                   u16(w.p2_hi), u16(w.p2_lo),
+                                                   reinterpret_cast<float*>(base + w.part_b), dB, t, lora_rank, s));
+}
+
 size_t quaff_bwd_dx_outlier_workspace_bytes(int64_t t, int64_t c_out) {
     if (t <= 0 || c_out <= 0) return 0;
     return align_up((size_t)64 * c_out * 2) + 2 * align_up((size_t)quaff::kLoraParts * t * 64 * 2) + 256;
