@@ -70,8 +70,8 @@ struct DmaCfg {
     // a SIMD, the MFMAs go first and the LDS reads of the next sub-step follow the first half of them, so that the
     // wait at the top of the next sub-step finds every read landed (-1..-8 % measured).  With one wavefront per SIMD
     // (or only four MFMAs per sub-step) reads and MFMAs alternate one by one instead (bunching the reads, in any of
-    // three patterns tried, costs 5-15 % there: a wavefront reads about 5 KiB per sub-step and nothing else covers
-    // the LDS pipe while it waits).
+    // three patterns tried, costs 5-15 % there; measured, the cause is not established: LDS bandwidth, about
+    // 240 bytes per clock and compute unit, is not it).
     static constexpr bool MFMA_FIRST = NW >= 8 && TM * TN >= 6;
     // wide-stage variant (gemm_mainloop_dma128): 128 contraction bytes per row, one direct load fills 8 rows
     static constexpr int WSTAGE_BYTES = (BM + BN) * 128, A_WBYTES = BM * 128;
