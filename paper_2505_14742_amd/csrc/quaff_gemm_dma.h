@@ -16,6 +16,42 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) f32x4 lds_f32x4;
 typedef __attribute__((address_space(3))) float lds_f32;
 
+// One direct-to-LDS load: 64 lanes x 16 bytes from per-lane global addresses to the 1 KiB of LDS that starts at `dst`
+// (the same for all lanes).  Issued as inline assembly on purpose: behind the compiler's own builtin every later wait
+// for an LDS read becomes a wait for ALL outstanding LDS reads (its counter model treats the load as a flat access that
+// may return out of order), which stalls a wavefront for a full LDS latency at the top of every contraction sub-step;
+// behind this form the waits are exact (lgkmcnt(2..6)).  The loads' own completion is tracked by hand anyway
+// (QUAFF_WAIT_VMCNT + barrier).  M0 holds the LDS address; the compiler keeps nothing in M0 across statements here.
+// ASM = false keeps the builtin: with exact waits the tile with one wavefront per SIMD is 2-6 % slower, the tiles that
+// issue their MFMAs first (their reads have landed by the time of the wait anyway) are unchanged, and the 8-wavefront
+// 256x128 tile is 3-6 % faster (all measured).
+// (M0 is named as clobbered although the compiler calls it reserved: a kernel that takes this form issues every
+// direct load this way, so nothing of the compiler's lives in M0.)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+template <bool ASM>
+__device__ __forceinline__ void dma_load_16(const void* src, __attribute__((address_space(3))) int8_t* dst) {
+    if constexpr (ASM) {
+        const uint32_t d = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)dst);
+        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(d) : "memory", "m0");
+    } else {
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                         (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+    }
+}
+// 64 lanes x 4 bytes to the 256 bytes of LDS that start at `dst`
+template <bool ASM>
+__device__ __forceinline__ void dma_load_4(const void* src, __attribute__((address_space(3))) int8_t* dst) {
+    if constexpr (ASM) {
+        const uint32_t d = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)dst);
+        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(src), "s"(d) : "memory", "m0");
+    } else {
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                         (__attribute__((address_space(3))) void*)dst, 4, 0, 0);
+    }
+}
+#pragma clang diagnostic pop
+
 // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt = [3:0] and [15:14])
 #define QUAFF_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 
@@ -73,6 +109,7 @@ struct DmaCfg {
     // three patterns tried, costs 5-15 % there; measured, the cause is not established: LDS bandwidth, about
     // 240 bytes per clock and compute unit, is not it).
     static constexpr bool MFMA_FIRST = NW >= 8 && TM * TN >= 6;
+    static constexpr bool DMA_ASM = NW >= 8 && !MFMA_FIRST;      // see dma_load_16: only the 256x128 tile gains (3-6 %)
     // wide-stage variant (gemm_mainloop_dma128): 128 contraction bytes per row, one direct load fills 8 rows
     static constexpr int WSTAGE_BYTES = (BM + BN) * 128, A_WBYTES = BM * 128;
     static constexpr int NGROUP_W = (BM + BN) / 8, NLOAD_W = (NGROUP_W + NW - 1) / NW;
@@ -125,8 +162,7 @@ __device__ __forceinline__ void gemm_mainloop_dma(const int8_t* __restrict__ gA,
             const bool isA = q < C::A_BYTES / 1024;
             const int8_t* src = (isA ? gA + k0 : gB + kb) + voff[j];
             lds_i8* dst = dma + stage * C::STAGE_BYTES + q * 1024;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                             (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+            dma_load_16<C::DMA_ASM>(src, dst);
         }
     };
     auto read_frags = [&](int stage, int ks, i32x4 (&fa)[TM], i32x4 (&fb)[TN]) {
@@ -212,8 +248,7 @@ __device__ __forceinline__ void gemm_mainloop_dma128(const int8_t* __restrict__ 
             const bool isA = q < C::BM_ / 8;
             const int8_t* src = (isA ? pa : pb) + voff[j];
             lds_i8* dst = dma + stage * C::WSTAGE_BYTES + q * 1024;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                             (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+            dma_load_16<C::DMA_ASM>(src, dst);
         }
     };
     auto read_frags = [&](int stage, int ks, i32x4 (&fa)[TM], i32x4 (&fb)[TN]) {
@@ -339,8 +374,7 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
     const int ld_r = lane >> 2, ld_chunk = (lane & 3) ^ ((lane >> 4) & 3);
     auto fill = [&](int lds_off, int nrows, auto src_of) {
         for (int q = wave; q < nrows / 16; q += C::NW)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src_of(q * 16 + ld_r),
-                                             (__attribute__((address_space(3))) void*)(dma + lds_off + q * 1024), 16, 0, 0);
+            dma_load_16<C::DMA_ASM>(src_of(q * 16 + ld_r), dma + lds_off + q * 1024);
     };
     auto a_row = [&](int local) { int64_t r = m0 + local; return r < g.M ? r : g.M - 1; };   // clamped: never stored
     auto b_row = [&](int local) { int64_t r = n0 + local; return r < g.N ? r : g.N - 1; };
@@ -392,8 +426,7 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
                 if (base == nullptr) continue;
                 src = base + b_row(qb * 64 + lane);
             }
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                             (__attribute__((address_space(3))) void*)(dma + C::EPI_LIMIT + q * 256), 4, 0, 0);
+            dma_load_4<C::DMA_ASM>(src, dma + C::EPI_LIMIT + q * 256);
         }
     }
     const lds_i8* rs_plane = rd + C::EPI_LIMIT;

@@ -298,6 +298,7 @@ EDGE_CASES = [
     EdgeCase("very_wide_out_n70_r32", 1024, 256, 16384, list(range(2, 256, 3))[:70], 32),
     EdgeCase("mid_out_n200_r16", 2048, 256, 4096, list(range(0, 250))[:200], 16),
     EdgeCase("mid_out_n130_r64", 2048, 256, 4096, list(range(0, 256, 1))[60:190], 64),
+    EdgeCase("mid_in_short_contraction", 2048, 4096, 128, [5, 4000], 16),     # input-gradient product on the 256x128 tile
 ]
 
 
