@@ -106,8 +106,9 @@ struct DmaCfg {
     // a SIMD, the MFMAs go first and the LDS reads of the next sub-step follow the first half of them, so that the
     // wait at the top of the next sub-step finds every read landed (-1..-8 % measured).  With one wavefront per SIMD
     // (or only four MFMAs per sub-step) reads and MFMAs alternate one by one instead (bunching the reads, in any of
-    // three patterns tried, costs 5-15 % there; measured, the cause is not established: LDS bandwidth, about
-    // 240 bytes per clock and compute unit, is not it).
+    // three patterns tried, costs 5-15 % there; that tile is bound by the delivery of its operands into LDS, about
+    // 53 bytes per clock and compute unit at the full MFMA rate against about 40 that the direct-load path sustains,
+    // not by LDS reads).
     static constexpr bool MFMA_FIRST = NW >= 8 && TM * TN >= 6;
     static constexpr bool DMA_ASM = NW >= 8 && !MFMA_FIRST;      // see dma_load_16: only the 256x128 tile gains (3-6 %)
     // wide-stage variant (gemm_mainloop_dma128): 128 contraction bytes per row, one direct load fills 8 rows
