@@ -32,31 +32,34 @@ quant_lora_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx,
     }
 }
 
-// One pass over dY for both results.  A workgroup of 16 wavefronts owns 8 rows; wavefront w holds the 32-column steps
-// of its slice of the contraction range in registers in the MFMA operand layout (lane (m, g): row m, eight columns of
-// group g; the rows 8..15 of the 16-row MFMA stay zero), so the same registers feed the down-projection and, once the
-// row maxima have been exchanged through LDS, the quantizer.  Wavefronts 0-7 and 8-15 produce the two parts of T.
-// NSTEP (even) = steps per wavefront; the host picks the smallest instantiation with 8 * 32 * NSTEP >= cp
-// (rows of up to 5120 columns).
+// One pass over dY for both results.  A workgroup of 16 wavefronts owns 8 rows; wavefront w holds its slice of the
+// contraction range in registers, 64 columns per step: lane (m, g) keeps row m % 8, columns 32 (m / 8) + 8 g .. + 7 of
+// the step, so every lane holds data and a row's 64 columns are one 128-byte line.  As the A operand of the 16-row
+// MFMA this is rows 0..7 over the first 32 columns of the step stacked on the same rows over the second 32; two MFMAs
+// per step, one with each half of L as the B operand, leave the first half's products in result rows 0..7 of the one
+// and the second half's in rows 8..15 of the other (the remaining result rows are products of mismatched halves and are
+// dropped).  The same registers then feed the quantizer, once the row maxima have been exchanged through LDS.
+// Wavefronts 0-7 and 8-15 produce the two parts of T.  NSTEP = steps per wavefront; the host picks the smallest
+// instantiation with 8 * 64 * NSTEP >= cp.
 template <int R16, int NSTEP>
 __global__ void __launch_bounds__(64 * kLoraWaves)
 quant_lora_rows8_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx, const float* __restrict__ cs,
                         int8_t* __restrict__ Xq, float* __restrict__ delta, const uint16_t* __restrict__ L, float scale,
                         uint16_t* __restrict__ T_hi, uint16_t* __restrict__ T_lo) {
-    static_assert(kLoraParts == 2 && kLoraWaves == 16 && NSTEP % 2 == 0, "two parts of eight wavefronts each");
+    static_assert(kLoraParts == 2 && kLoraWaves == 16, "two parts of eight wavefronts each");
     constexpr int r = R16 * 16;
-    constexpr int BU = R16 == 1 ? 6 : 2;           // steps whose B operands are in flight together
+    constexpr int BU = 3;                          // steps whose B operands are in flight together
     __shared__ float red[kLoraWaves][R16][32][4];
     __shared__ float rmax[kLoraWaves][8];
     // The eight rows of a wavefront share their column scales, so a scale vector fetched from global memory would be
     // requested by eight lanes at once, twice per element (maximum pass, code pass): the texture path would then
-    // carry four times the traffic of dY itself.  The workgroup keeps one copy of cs in LDS instead.
+    // carry several times the traffic of dY itself.  The workgroup keeps one copy of cs in LDS instead.
     extern __shared__ float cs_copy[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 15, g = lane >> 4;
     const int64_t row = (int64_t)blockIdx.x * 8 + (m & 7);
-    const bool active = m < 8 && row < t;
-    const uint16_t* xrow = X + (row < t ? row : 0) * ldx;
+    const bool live = row < t;
+    const uint16_t* xrow = X + (live ? row : 0) * ldx;
 
     const int part = wave >> 3;
     const int cp = ((c + kLoraParts * 64 - 1) / (kLoraParts * 64)) * 64;
@@ -64,35 +67,45 @@ quant_lora_rows8_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_
     const int kw = ((cp + 8 * 64 - 1) / (8 * 64)) * 64;
     const int kbeg = cbeg + (wave & 7) * kw, kend = kbeg + kw < cend ? kbeg + kw : cend;
 
-    // this lane's eight columns of step u (two consecutive steps share whole 128-byte lines, as in lora_down_body)
-    auto col_of = [&](int u) { return kbeg + (u >> 1) * 64 + (u & 1) * 8 + g * 16; };
+    // this lane's eight columns of step u, and the eight columns of L it supplies for the step's first / second half
+    auto col_of = [&](int u) { return kbeg + u * 64 + (m >> 3) * 32 + g * 8; };
+    auto lcol_of = [&](int u, int half) { return kbeg + u * 64 + half * 32 + g * 8; };
     u32x4 xa[NSTEP];
 #pragma unroll
     for (int u = 0; u < NSTEP; ++u) {
         const int k = col_of(u);
         xa[u] = (u32x4){0, 0, 0, 0};
-        if (active && k < kend) xa[u] = *reinterpret_cast<const u32x4*>(xrow + k);
+        if (live && k < kend) xa[u] = *reinterpret_cast<const u32x4*>(xrow + k);
     }
-    f32x4 acc[R16];
+    f32x4 acc0[R16], acc1[R16];                    // first-half products (rows 0..7 valid), second-half (rows 8..15)
 #pragma unroll
-    for (int b = 0; b < R16; ++b) acc[b] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int b = 0; b < R16; ++b) acc0[b] = acc1[b] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int u0 = 0; u0 < NSTEP; u0 += BU) {
-        u32x4 lb[BU][R16];
+        u32x4 lb[BU][2][R16];
 #pragma unroll
-        for (int uu = 0; uu < BU; ++uu) {
-            const int k = col_of(u0 + uu), kc = k < kend ? k : c - 8;   // clamped: multiplied by a cleared x fragment
+        for (int uu = 0; uu < BU; ++uu)
 #pragma unroll
-            for (int b = 0; b < R16; ++b)
-                if (u0 + uu < NSTEP) lb[uu][b] = *reinterpret_cast<const u32x4*>(L + (int64_t)(b * 16 + m) * c + kc);
-        }
+            for (int h = 0; h < 2; ++h) {
+                const int k = lcol_of(u0 + uu, h), kc = k < kend ? k : c - 8;
+#pragma unroll
+                for (int b = 0; b < R16; ++b) {
+                    lb[uu][h][b] = (u32x4){0, 0, 0, 0};     // columns past the slice contribute nothing
+                    if (u0 + uu < NSTEP) {
+                        const u32x4 v = *reinterpret_cast<const u32x4*>(L + (int64_t)(b * 16 + m) * c + kc);
+                        if (k < kend) lb[uu][h][b] = v;
+                    }
+                }
+            }
 #pragma unroll
         for (int uu = 0; uu < BU; ++uu)
 #pragma unroll
             for (int b = 0; b < R16; ++b)
-                if (u0 + uu < NSTEP)
-                    acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xa[u0 + uu]),
-                                                                     __builtin_bit_cast(bf16x8, lb[uu][b]), acc[b], 0, 0, 0);
+                if (u0 + uu < NSTEP) {
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, xa[u0 + uu]);
+                    acc0[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, lb[uu][0][b]), acc0[b], 0, 0, 0);
+                    acc1[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, lb[uu][1][b]), acc1[b], 0, 0, 0);
+                }
     }
     for (int i = threadIdx.x * 4; i < c; i += 64 * kLoraWaves * 4)     // c is a multiple of 16
         *reinterpret_cast<f32x4*>(cs_copy + i) = *reinterpret_cast<const f32x4*>(cs + i);
@@ -100,7 +113,7 @@ quant_lora_rows8_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_
     const lds_float* csl = (const lds_float*)cs_copy;
     // row maxima of dY * cs over this wavefront's slice
     float mx = 0.0f;
-    if (active) {
+    if (live) {
 #pragma unroll
         for (int u = 0; u < NSTEP; ++u) {
             const int k = col_of(u);
@@ -112,24 +125,28 @@ quant_lora_rows8_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_
             }
         }
     }
+    mx = fmaxf(mx, __shfl_xor(mx, 8, 64));       // the two column halves of a row
     mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     if (lane < 8) rmax[wave][lane] = mx;
-    // element v of lane (m, g) of the MFMA result is T[4 g + v][16 b + m]: rows 0..7 live in the lane groups g < 2
-    if (g < 2)
+    // Element v of lane (p, g) of an MFMA result is row 4 g + v, column 16 b + p.  Row i < 8 of acc0 (lane groups
+    // g < 2) and row i + 8 of acc1 (lane groups g >= 2, 32 lanes further on) are the two halves of T[i]'s partial sum.
 #pragma unroll
-        for (int b = 0; b < R16; ++b)
+    for (int b = 0; b < R16; ++b)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) red[wave][b][lane][v] = acc[b][v];
+        for (int v = 0; v < 4; ++v) {
+            const float second = __shfl_down(acc1[b][v], 32, 64);
+            if (g < 2) red[wave][b][lane][v] = acc0[b][v] + second;
+        }
     __syncthreads();
 
-    if (active) {
+    if (live) {
         float mrow = 0.0f;
 #pragma unroll
-        for (int w = 0; w < kLoraWaves; ++w) mrow = fmaxf(mrow, rmax[w][m]);
+        for (int w = 0; w < kLoraWaves; ++w) mrow = fmaxf(mrow, rmax[w][m & 7]);
         float d, cc;
         rtn_steps(mrow, d, cc);
-        if (wave == 0 && g == 0) delta[row] = d;
+        if (wave == 0 && lane < 8) delta[row] = d;
         int8_t* qrow = Xq + row * (int64_t)c;
 #pragma unroll
         for (int u = 0; u < NSTEP; ++u) {
@@ -163,14 +180,16 @@ template <int R16>
 static bool launch_rows8(const uint16_t* X, int64_t t, int c, int64_t ldx, const float* cs, int8_t* Xq, float* delta,
                          const uint16_t* L, float scale, uint16_t* T_hi, uint16_t* T_lo, hipStream_t stream) {
     const int cp = ((c + kLoraParts * 64 - 1) / (kLoraParts * 64)) * 64;
-    const int nstep = ((cp + 8 * 64 - 1) / (8 * 64)) * 2;    // 32-column steps per wavefront
+    const int nstep = (cp + 8 * 64 - 1) / (8 * 64);          // 64-column steps per wavefront
     const dim3 grid((unsigned)((t + 7) / 8)), block(64 * kLoraWaves);
 #define QUAFF_R8(NS)                                                                                                  \
     hipLaunchKernelGGL((quant_lora_rows8_kernel<R16, NS>), grid, block, (size_t)c * 4, stream, X, t, c, ldx, cs, Xq, delta, L,   \
                        scale, T_hi, T_lo)
-    // longer slices (18 steps = 9216 columns were tried: 124 registers, 31 us against 26 us) stay with the two-role launch
-    if (nstep <= 6) QUAFF_R8(6);
-    else if (nstep <= 10) QUAFF_R8(10);
+    // Longer rows stay with the two-role launch: at 9216 columns (nine steps, 83 registers, one workgroup per compute
+    // unit) this one takes 30 us against 28: with a single workgroup per unit its load, compute and store phases do not
+    // overlap, while the two-role launch keeps many short workgroups in flight.
+    if (nstep <= 3) QUAFF_R8(3);
+    else if (nstep <= 5) QUAFF_R8(5);
     else return false;
 #undef QUAFF_R8
     return true;
