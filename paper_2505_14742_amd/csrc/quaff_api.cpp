@@ -1,6 +1,8 @@
 // C ABI of libquaff: argument checking, workspace carving and kernel launches.  No computation happens here.
 #include "../../include/quaff.h"
 #include "quaff_internal.h"
+#include <functional>
+#include <mutex>
 
 namespace {
 
@@ -251,7 +253,8 @@ int quaff_linear_fwd_acc(const int8_t* Xq, const int8_t* xq_O, int64_t t, const 
 static int linear_bwd_dx_impl(const uint16_t* dY, int64_t t, int64_t lddy, const void* Wq_packed, const float* delta_w,
                               int64_t c_in, int64_t c_out, const uint16_t* lora_A, const uint16_t* lora_B,
                               int32_t lora_rank, float lora_scale, float* dX, uint16_t* dX16, int64_t lddx,
-                              void* workspace, size_t workspace_bytes, void* stream) {
+                              void* workspace, size_t workspace_bytes, void* stream,
+                              const std::function<int()>* before_product = nullptr) {
     if (!dY || !Wq_packed || !delta_w || (!dX && !dX16)) return QUAFF_ERR_NULL;
     if (dX16 && c_out % 64 != 0) return QUAFF_ERR_SHAPE;
     if (dX16 && (!aligned16(dX16) || lddx % 8 != 0)) return QUAFF_ERR_ALIGN;
@@ -295,6 +298,9 @@ static int linear_bwd_dx_impl(const uint16_t* dY, int64_t t, int64_t lddy, const
         if (st != QUAFF_OK) return st;
     }
     g.C = dX; g.C16 = dX16; g.ldc = lddx;
+    // (the one-call backward step forks its weight-gradient work here: the quantizer and the down-projection are
+    // enqueued, the long product is not yet)
+    if (before_product && (st = (*before_product)()) != QUAFF_OK) return st;
     return hip_status(quaff::launch_gemm(g, false, s));
 }
 
@@ -369,6 +375,28 @@ int quaff_lora_bwd_weights(const uint16_t* X, int64_t ldx, const uint16_t* dY, i
                                                    reinterpret_cast<float*>(base + w.part_b), dB, t, lora_rank, s));
 }
 
+namespace {
+// A second stream per device for quaff_linear_bwd_step: the LoRA weight gradients (memory-bound, short kernels) do not
+// depend on the input-gradient product (long, MFMA-bound) and run beside it, forked and joined with events so that
+// everything stays ordered on the caller's stream.  Created on first use, default priority, kept for the process.
+struct SideStream { hipStream_t stream = nullptr; hipEvent_t fork = nullptr, join = nullptr; bool ok = false, tried = false; };
+SideStream* side_stream() {
+    static std::mutex mu;
+    static SideStream per_device[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    SideStream& ss = per_device[dev];
+    if (!ss.tried) {
+        ss.tried = true;
+        ss.ok = hipStreamCreateWithFlags(&ss.stream, hipStreamNonBlocking) == hipSuccess &&
+                hipEventCreateWithFlags(&ss.fork, hipEventDisableTiming) == hipSuccess &&
+                hipEventCreateWithFlags(&ss.join, hipEventDisableTiming) == hipSuccess;
+    }
+    return ss.ok ? &ss : nullptr;
+}
+}  // namespace
+
 size_t quaff_bwd_step_workspace_bytes(int64_t t, int64_t c_in, int64_t c_out, int32_t lora_rank) {
     if (t <= 0 || c_in <= 0 || c_out <= 0 || lora_rank <= 0) return 0;
     return ws_bwd(t, c_out, lora_rank).total + ws_grad(t, c_in, c_out, lora_rank).total + 256;
@@ -384,27 +412,47 @@ int quaff_linear_bwd_step(const uint16_t* dY, int64_t t, int64_t lddy, const uin
     const GradWs w = ws_grad(t, c_in, c_out, lora_rank);
     if (!workspace || workspace_bytes < wb.total + w.total) return QUAFF_ERR_WORKSPACE;
     if (!aligned16(X) || !aligned16(workspace) || ldx % 8 != 0) return QUAFF_ERR_ALIGN;
-    // dX first: it leaves T1 = scale dY B^T (hi / lo parts of the down-projection) in its part of the workspace
-    int st = linear_bwd_dx_impl(dY, t, lddy, Wq_packed, delta_w, c_in, c_out, lora_A, lora_B, lora_rank, lora_scale, dX,
-                                nullptr, lddx, workspace, wb.total, stream);
-    if (st != QUAFF_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     char* bwd = static_cast<char*>(workspace);
     char* base = bwd + wb.total;
     auto u16 = [&](size_t off) { return reinterpret_cast<uint16_t*>(base + off); };
     uint16_t* t1_hi = reinterpret_cast<uint16_t*>(bwd + wb.t_hi);
     uint16_t* t1_lo = reinterpret_cast<uint16_t*>(bwd + wb.t_lo);
-    // T2 = scale X A, then the two products of quaff_lora_bwd_weights
-    st = hip_status(quaff::launch_lora_down(X, t, c_in, ldx, lora_A, false, lora_rank, lora_scale, u16(w.t2_hi),
-                                            u16(w.t2_lo), nullptr, nullptr, 0, 0, s, u16(w.at)));
+    // T2 = scale X A, then the two products of quaff_lora_bwd_weights, on stream `gs`; T1 = scale dY B^T (hi / lo parts)
+    // is what the dX call leaves in its part of the workspace
+    auto weight_grads = [&](hipStream_t gs) -> int {
+        int st = hip_status(quaff::launch_lora_down(X, t, c_in, ldx, lora_A, false, lora_rank, lora_scale, u16(w.t2_hi),
+                                                    u16(w.t2_lo), nullptr, nullptr, 0, 0, gs, u16(w.at)));
+        if (st != QUAFF_OK) return st;
+        st = hip_status(quaff::launch_lora_grad_prep(t1_hi, t1_lo, u16(w.p1_hi), u16(w.p1_lo), u16(w.t2_hi),
+                                                     u16(w.t2_lo), u16(w.p2_hi), u16(w.p2_lo), t, lora_rank, gs));
+        if (st != QUAFF_OK) return st;
+        return hip_status(quaff::launch_lora_grad_pair(X, ldx, c_in, u16(w.p1_hi), u16(w.p1_lo),
+                                                       reinterpret_cast<float*>(base + w.part_a), dA, dY, lddy, c_out,
+                                                       u16(w.p2_hi), u16(w.p2_lo),
+                                                       reinterpret_cast<float*>(base + w.part_b), dB, t, lora_rank, gs));
+    };
+    SideStream* side = side_stream();
+    bool forked = false;
+    const std::function<int()> fork = [&]() -> int {
+        if (!side) return QUAFF_OK;
+        // the weight gradients start once T1 exists and run beside the input-gradient product
+        int st = hip_status(hipEventRecord(side->fork, s));
+        if (st != QUAFF_OK) return st;
+        if ((st = hip_status(hipStreamWaitEvent(side->stream, side->fork, 0))) != QUAFF_OK) return st;
+        forked = true;
+        if ((st = weight_grads(side->stream)) != QUAFF_OK) return st;
+        return hip_status(hipEventRecord(side->join, side->stream));
+    };
+    int st = linear_bwd_dx_impl(dY, t, lddy, Wq_packed, delta_w, c_in, c_out, lora_A, lora_B, lora_rank, lora_scale, dX,
+                                nullptr, lddx, workspace, wb.total, stream, &fork);
+    if (forked) {
+        // whatever happened, the caller's stream waits for what was put on the side stream
+        int st2 = hip_status(hipStreamWaitEvent(s, side->join, 0));
+        return st != QUAFF_OK ? st : st2;
+    }
     if (st != QUAFF_OK) return st;
-    st = hip_status(quaff::launch_lora_grad_prep(t1_hi, t1_lo, u16(w.p1_hi), u16(w.p1_lo), u16(w.t2_hi), u16(w.t2_lo),
-                                                 u16(w.p2_hi), u16(w.p2_lo), t, lora_rank, s));
-    if (st != QUAFF_OK) return st;
-    return hip_status(quaff::launch_lora_grad_pair(X, ldx, c_in, u16(w.p1_hi), u16(w.p1_lo),
-                                                   reinterpret_cast<float*>(base + w.part_a), dA, dY, lddy, c_out,
-                                                   u16(w.p2_hi), u16(w.p2_lo),
-                                                   reinterpret_cast<float*>(base + w.part_b), dB, t, lora_rank, s));
+    return weight_grads(s);
 }
 
 size_t quaff_bwd_dx_outlier_workspace_bytes(int64_t t, int64_t c_out) {
