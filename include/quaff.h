@@ -229,7 +229,8 @@ int quaff_lora_bwd_weights(const uint16_t* X, int64_t ldx, const uint16_t* dY, i
  * The weight gradients do not depend on the input-gradient product and are enqueued on a second stream that the
  * library keeps per device (created at the first call, default priority), forked from and joined back into `stream`
  * with events: towards the caller everything is ordered on `stream` as usual.  If that stream cannot be created the
- * call runs everything on `stream`.
+ * call runs everything on `stream`.  The second stream and its events are shared by all calls on a device: do not
+ * issue this call for one device from several host threads at once.
  */
 size_t quaff_bwd_step_workspace_bytes(int64_t t, int64_t c_in, int64_t c_out, int32_t lora_rank);
 int quaff_linear_bwd_step(const uint16_t* dY, int64_t t, int64_t lddy, const uint16_t* X, int64_t ldx,
