@@ -285,7 +285,10 @@ def main():
                      "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": round(gemm_tops / INT8_PEAK_TOPS, 4),
                      "traffic": gemm_traffic, "traffic_unit": "bytes per GEMM launch (rocprofv3 FETCH_SIZE + "
                      "WRITE_SIZE, scaled by the copy kernel; profiles/gemm_i8_hbm_traffic_phi3_attention.md)",
-                     "algorithmic_bytes_per_launch": round(gemm_bytes / len(order)), "per_shape": gemm_shapes},
+                     "algorithmic_bytes_per_launch": round(gemm_bytes / len(order)), "per_shape": gemm_shapes,
+                     "note": "priced against the INT8 MFMA peak as a contraction; the 128x192-tile launches (2048 x 3072 "
+                             "outputs: one tile per compute unit) are held back by operand delivery from L2 into LDS, "
+                             "the 256x288-tile launch by the power-limited MFMA clock (measured_ceilings)"},
         "kernels": kernels,
         "kernels_with_separate_calls": kernels_separate,
     }
