@@ -24,6 +24,8 @@ bool dims_ok(int64_t t, int64_t c_in, int64_t c_out) {
            c_in % 16 == 0 && c_out % 16 == 0;
 }
 bool rank_ok(int32_t r) { return r == 0 || (r > 0 && r <= 64 && r % 16 == 0); }
+// leading dimension of an output of the products (the store addressing keeps four rows in a 32-bit offset)
+bool out_ld_ok(int64_t ld, int64_t cols) { return ld >= cols && ld < ((int64_t)1 << 28); }
 
 // the packed weight codes as the B operand of the forward (c_out x c_in) or of the input-gradient product
 void set_weight_operand(quaff::GemmArgs& g, const void* packed, int64_t c_in, bool gradient) {
@@ -192,7 +194,7 @@ static int linear_fwd_impl(const int8_t* Xq, const float* delta_x, const int8_t*
     int st = fwd_common(Xq, delta_x, xq_O, t, Wq_packed, delta_w, c_in, c_out, what_int, delta_what, n_outlier, g);
     if (st != QUAFF_OK) return st;
     if (!delta_x || !delta_w || (!Y && !Y16) || (n_outlier > 0 && !delta_what)) return QUAFF_ERR_NULL;
-    if (!rank_ok(lora_rank) || ldy < c_out) return QUAFF_ERR_SHAPE;
+    if (!rank_ok(lora_rank) || !out_ld_ok(ldy, c_out)) return QUAFF_ERR_SHAPE;
     if (Y16 && (c_in % 64 != 0 || n_outlier > 128)) return QUAFF_ERR_SHAPE;
     if (Y16 && (!aligned16(Y16) || ldy % 8 != 0)) return QUAFF_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -259,7 +261,7 @@ static int linear_bwd_dx_impl(const uint16_t* dY, int64_t t, int64_t lddy, const
     if (dX16 && c_out % 64 != 0) return QUAFF_ERR_SHAPE;
     if (dX16 && (!aligned16(dX16) || lddx % 8 != 0)) return QUAFF_ERR_ALIGN;
     if (lora_rank > 0 && (!lora_A || !lora_B)) return QUAFF_ERR_NULL;
-    if (!dims_ok(t, c_in, c_out) || !rank_ok(lora_rank) || lddy < c_out || lddx < c_in) return QUAFF_ERR_SHAPE;
+    if (!dims_ok(t, c_in, c_out) || !rank_ok(lora_rank) || lddy < c_out || !out_ld_ok(lddx, c_in)) return QUAFF_ERR_SHAPE;
     BwdWs w = ws_bwd(t, c_out, lora_rank);
     if (!workspace || workspace_bytes < w.total) return QUAFF_ERR_WORKSPACE;
     if (!aligned16(dY) || !aligned16(Wq_packed) || !aligned16(delta_w) || !aligned16(workspace) || lddy % 8 != 0 ||
@@ -544,7 +546,7 @@ int quaff_linear_fwd_step(const uint16_t* X, int64_t t, int64_t c_in, int64_t ld
     if (!X || !O || !W_O || !wmax_O || !s_O || !what_int || !delta_what || !Xq || !delta_x || !Wq_packed || !delta_w ||
         !lora_A || !lora_B || !Y)
         return QUAFF_ERR_NULL;
-    if (!dims_ok(t, c_in, c_out) || n_outlier > c_in || ldx < c_in || ldy < c_out || !(gamma >= 0.0f && gamma <= 1.0f))
+    if (!dims_ok(t, c_in, c_out) || n_outlier > c_in || ldx < c_in || !out_ld_ok(ldy, c_out) || !(gamma >= 0.0f && gamma <= 1.0f))
         return QUAFF_ERR_SHAPE;
     if (!aligned16(X) || !aligned16(what_int) || !aligned16(Xq) || !aligned16(colscale) || !aligned16(xq_O) ||
         !aligned16(Wq_packed) || !aligned16(lora_A) || !aligned16(lora_B) || ldx % 8 != 0)

@@ -7,6 +7,7 @@
 // See quaff_gemm.hip for the computation.
 #pragma once
 #include "quaff_gemm_kernel.h"
+#include <type_traits>
 
 namespace quaff {
 
@@ -436,86 +437,41 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
     const bool has_cs = g.col_scale != nullptr, has_cs2 = nk > 0;
     landed();
 
-    // ---- phase A
+    // fp32 store of one 32x32 block (this lane: 16 rows of one column).  The block's first element is the same for
+    // every lane, so its address stays in scalar registers (one per stored row) and the lane adds a single 32-bit
+    // offset: the stores then need one address register instead of sixteen 64-bit ones.
+    const uint32_t store_voff = (uint32_t)(((int64_t)lhi * 4 * g.ldc + l32) * 4);   // ldc < 2^28, checked by the caller
+    typedef __attribute__((address_space(1))) char gchar;
+    typedef __attribute__((address_space(1))) float gfloat;
+    auto block_base = [&](int i, int j) {
+        const uint64_t first = reinterpret_cast<uint64_t>(g.C + (row0 + i * 32) * g.ldc + col0 + j * 32);
+        return (gchar*)(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(first >> 32)) << 32) |
+                        (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)first));
+    };
+    auto store_block_full = [&](int i, int j, const i32x16& bits) {
+        gchar* base = block_base(i, j);
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        if (row0 + i * 32 >= g.M) continue;
-        f32x4 rs[4];   // this lane's 16 output rows of the block are 4 runs of 4 consecutive rows
-#pragma unroll
-        for (int vg = 0; vg < 4; ++vg)
-            rs[vg] = *(const lds_f32x4*)(rs_plane + (wm * C::WM + i * 32 + vg * 8 + lhi * 4) * 4);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            if (col0 + j * 32 >= g.N) continue;
-            const int lcol = wn * C::WN + j * 32 + l32;
-            const float cs = has_cs ? *(const lds_f32*)(cs_plane + lcol * 4) : 1.0f;
-            const float cs2 = has_cs2 ? *(const lds_f32*)(cs2_plane + lcol * 4) : 0.0f;
-            i32x16 acc2;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc2[v] = 0;
-            for (int kk = 0; kk < nk; ++kk) {
-                const int off = kk * C::K2_PLANES_BYTES;
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks)
-                    acc2 = __builtin_amdgcn_mfma_i32_32x32x32_i8(frag(off, wm * C::WM + i * 32, ks * 2 + lhi),
-                                                                 frag(off + PLANE_A, wn * C::WN + j * 32, ks * 2 + lhi),
-                                                                 acc2, 0, 0, 0);
-            }
-            float prev[16];
-#pragma unroll
-            for (int v = 0; v < 16; ++v) prev[v] = 0.0f;
-            if constexpr (ACCUM) {
-                // this lane's 16 output elements of the block, as phase C addresses them (clamped: never stored)
-                const int64_t ib = row0 + i * 32, col = col0 + j * 32 + l32;
-                const int64_t cc = col < g.N ? col : g.N - 1;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    int64_t row = ib + (v >> 2) * 8 + lhi * 4 + (v & 3);
-                    prev[v] = g.C[(row < g.M ? row : g.M - 1) * g.ldc + cc];
-                }
-            }
+        for (int v = 0; v < 16; ++v)
+            *(gfloat*)(base + (int64_t)((v >> 2) * 8 + (v & 3)) * g.ldc * 4 + store_voff) = __int_as_float(bits[v]);
+    };
+    auto store_block = [&](int i, int j, const i32x16& bits) {
+        const int64_t ib = row0 + i * 32, jb = col0 + j * 32;
+        if (ib + 32 <= g.M && jb + 32 <= g.N) {
+            store_block_full(i, j, bits);
+        } else {
+            gchar* base = block_base(i, j);
+            const int64_t col = jb + l32;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                float inner = __builtin_fmaf((float)acc[i][j][v], cs, (float)acc2[v] * cs2);
-                acc[i][j][v] = __float_as_int(rs[v >> 2][v & 3] * inner + prev[v]);
+                int64_t row = ib + (v >> 2) * 8 + lhi * 4 + (v & 3);
+                if (row < g.M && col < g.N)
+                    *(gfloat*)(base + (int64_t)((v >> 2) * 8 + (v & 3)) * g.ldc * 4 + store_voff) = __int_as_float(bits[v]);
             }
         }
-    }
+    };
 
-    // ---- phase B
-    for (int lc = 0; lc < nl; ++lc) {
-        if (!(overlap && lc == 0)) {
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            __builtin_amdgcn_s_barrier();          // everybody has read what the next loads overwrite
-            asm volatile("" ::: "memory");
-            issue_lora(lc);
-            landed();
-        }
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            if (row0 + i * 32 >= g.M) continue;
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                if (col0 + j * 32 >= g.N) continue;
-                f32x16 c = __builtin_bit_cast(f32x16, acc[i][j]);
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {           // 16 columns of r per MFMA
-                    if (lc * 32 + h * 16 >= g.r) continue;
-                    const bf16x8 lb = __builtin_bit_cast(
-                        bf16x8, frag(lora_off + 2 * kLoraParts * PLANE_A, wn * C::WN + j * 32, h * 2 + lhi));
-#pragma unroll
-                    for (int pl = 0; pl < 2 * kLoraParts; ++pl)
-                        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(bf16x8, frag(lora_off + pl * PLANE_A, wm * C::WM + i * 32, h * 2 + lhi)),
-                            lb, c, 0, 0, 0);
-                }
-                acc[i][j] = __builtin_bit_cast(i32x16, c);
-            }
-        }
-    }
-
-    // ---- phase C
-    if constexpr (OUT16) {
+    // ---- bf16 form of the last phase (a lambda, so that each path above ends in its own copy of it)
+    auto out16_phase = [&]() {
         // bf16 output (round to nearest even).  A 32x32 block is only 64 bytes wide in bf16, so the wavefront's
         // 32 x WN strip is first assembled in a private piece of the idle LDS ring (neighbouring lanes swap half of
         // their rows so that a lane writes two adjacent columns as one 32-bit word) and then leaves as 16-byte
@@ -560,26 +516,219 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
             }
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the strip is reused by the next block row
         }
+    };
+
+    // (bf16 output: the tile shapes that take their blocks one by one keep the phases below - the same arithmetic,
+    // and the output strips need the registers)
+    constexpr bool PIPE = C::NW <= 8 && TM * TN <= 6;
+    if ((!OUT16 || PIPE) && overlap && nl <= 1 && m0 + BM <= g.M && n0 + BN <= g.N) {
+        // ---- the usual case (a whole tile, every staged operand fits side by side, r <= 32): one pass per 32x32 block, whose
+        // stores leave while the next block computes.  Where the registers allow a second block in flight (at most
+        // 96 accumulator registers and two wavefronts per SIMD), the correction product and the low-rank product of
+        // the next block - the latter accumulated from zero, so that neither depends on the conversion arithmetic -
+        // are issued before the vector instructions of this block and run under them.  The other tile shapes take
+        // the blocks one by one (correction product, conversion, low-rank product onto the result): there the other
+        // wavefronts of the SIMD fill the gaps.  The scheduling barrier after each block bounds the live registers.
+        constexpr int L_PLANE = 2 * kLoraParts * PLANE_A;
+        constexpr int NB = TM * TN;
+        auto block_k2 = [&](int i, int j, i32x16& acc2) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc2[v] = 0;
+            for (int kk = 0; kk < nk; ++kk) {
+                const int off = kk * C::K2_PLANES_BYTES;
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+                    acc2 = __builtin_amdgcn_mfma_i32_32x32x32_i8(frag(off, wm * C::WM + i * 32, ks * 2 + lhi),
+                                                                 frag(off + PLANE_A, wn * C::WN + j * 32, ks * 2 + lhi),
+                                                                 acc2, 0, 0, 0);
+            }
+        };
+        auto block_lora = [&](int i, int j, f32x16& c) {   // c += T L^T
+            if (nl == 0) return;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {           // 16 columns of r per MFMA
+                if (h * 16 >= g.r) continue;
+                const bf16x8 lb = __builtin_bit_cast(bf16x8, frag(lora_off + L_PLANE, wn * C::WN + j * 32, h * 2 + lhi));
+#pragma unroll
+                for (int pl = 0; pl < 2 * kLoraParts; ++pl)
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        __builtin_bit_cast(bf16x8, frag(lora_off + pl * PLANE_A, wm * C::WM + i * 32, h * 2 + lhi)), lb,
+                        c, 0, 0, 0);
+            }
+        };
+        // c = row_scale * (acc * cs + acc2 * cs2) [+ c];  MODE 2: both column scales, 1: cs only, 0: neither,
+        // 3: whatever is there (a missing scale is 1 or 0: the bits of the special forms, more instructions)
+        auto block_dequant = [&](int i, int j, const f32x4 (&rs)[4], const i32x16& acc2, f32x16& c, auto add, auto mode) {
+            constexpr bool ADD = decltype(add)::value;
+            constexpr int MODE = decltype(mode)::value;
+            const int lcol = wn * C::WN + j * 32 + l32;
+            const float cs = MODE >= 1 && has_cs ? *(const lds_f32*)(cs_plane + lcol * 4) : 1.0f;
+            const float cs2 = MODE == 2 || (MODE == 3 && has_cs2) ? *(const lds_f32*)(cs2_plane + lcol * 4) : 0.0f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const float a = (float)acc[i][j][v];
+                const float inner = MODE >= 2 ? __builtin_fmaf(a, cs, (float)acc2[v] * cs2) : MODE == 1 ? a * cs : a;
+                const float r = rs[v >> 2][v & 3];
+                c[v] = ADD ? __builtin_fmaf(r, inner, c[v]) : r * inner;
+            }
+        };
+        auto block_prev = [&](int i, int j, f32x16& c) {   // what C holds, as store_block addresses it
+            const gchar* base = block_base(i, j);
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                c[v] = *(const gfloat*)(base + (int64_t)((v >> 2) * 8 + (v & 3)) * g.ldc * 4 + store_voff);
+        };
+        auto block_out = [&](int i, int j, const f32x16& c) {
+            if constexpr (OUT16) {
+                acc[i][j] = __builtin_bit_cast(i32x16, c);
+            } else {
+                store_block_full(i, j, __builtin_bit_cast(i32x16, c));
+            }
+        };
+        i32x16 acc2[PIPE ? 2 : 1];
+        f32x16 low[PIPE ? 2 : 1];
+        f32x4 rs[4];   // this lane's 16 output rows of a block are 4 runs of 4 consecutive rows
+        auto block_ahead = [&](int b) {   // (blocks past the edge of C read staged rows that exist)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) low[b & 1][v] = 0.0f;
+            block_k2(b / TN, b % TN, acc2[b & 1]);
+            block_lora(b / TN, b % TN, low[b & 1]);
+        };
+        auto run = [&](auto mode) {
+            if constexpr (PIPE && !OUT16) block_ahead(0);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const int i = b / TN, j = b % TN;
+                if (j == 0) {
+#pragma unroll
+                    for (int vg = 0; vg < 4; ++vg)
+                        rs[vg] = *(const lds_f32x4*)(rs_plane + (wm * C::WM + i * 32 + vg * 8 + lhi * 4) * 4);
+                }
+                if constexpr (PIPE && OUT16) {
+                    // the arithmetic of the pipelined form, one block at a time (the output strips need the registers)
+                    block_ahead(b);
+                    block_dequant(i, j, rs, acc2[b & 1], low[b & 1], std::true_type{}, mode);
+                    block_out(i, j, low[b & 1]);
+                } else if constexpr (PIPE) {
+                    if (b + 1 < NB) block_ahead(b + 1);
+                    f32x16& c = low[b & 1];
+                    if constexpr (ACCUM) {
+                        f32x16 prev;
+                        block_prev(i, j, prev);
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) c[v] += prev[v];
+                    }
+                    block_dequant(i, j, rs, acc2[b & 1], c, std::true_type{}, mode);
+                    block_out(i, j, c);
+                } else {
+                    f32x16& c = low[0];
+                    if constexpr (decltype(mode)::value >= 2) block_k2(i, j, acc2[0]);
+                    if constexpr (ACCUM) block_prev(i, j, c);
+                    block_dequant(i, j, rs, acc2[0], c, std::integral_constant<bool, ACCUM>{}, mode);
+                    block_lora(i, j, c);
+                    block_out(i, j, c);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if constexpr (OUT16) out16_phase();
+        };
+        if constexpr (OUT16) run(std::integral_constant<int, 3>{});   // one copy: the strips need the registers
+        else if (has_cs2) run(std::integral_constant<int, 2>{});
+        else if (has_cs) run(std::integral_constant<int, 1>{});
+        else run(std::integral_constant<int, 0>{});
+        return;
+    }
+    {
+        // ---- phase A
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            if (row0 + i * 32 >= g.M) continue;
+            f32x4 rs[4];   // this lane's 16 output rows of the block are 4 runs of 4 consecutive rows
+#pragma unroll
+            for (int vg = 0; vg < 4; ++vg)
+                rs[vg] = *(const lds_f32x4*)(rs_plane + (wm * C::WM + i * 32 + vg * 8 + lhi * 4) * 4);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                if (col0 + j * 32 >= g.N) continue;
+                const int lcol = wn * C::WN + j * 32 + l32;
+                const float cs = has_cs ? *(const lds_f32*)(cs_plane + lcol * 4) : 1.0f;
+                const float cs2 = has_cs2 ? *(const lds_f32*)(cs2_plane + lcol * 4) : 0.0f;
+                i32x16 acc2;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc2[v] = 0;
+                for (int kk = 0; kk < nk; ++kk) {
+                    const int off = kk * C::K2_PLANES_BYTES;
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks)
+                        acc2 = __builtin_amdgcn_mfma_i32_32x32x32_i8(frag(off, wm * C::WM + i * 32, ks * 2 + lhi),
+                                                                     frag(off + PLANE_A, wn * C::WN + j * 32, ks * 2 + lhi),
+                                                                     acc2, 0, 0, 0);
+                }
+                float prev[16];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) prev[v] = 0.0f;
+                if constexpr (ACCUM) {
+                    // this lane's 16 output elements of the block, as phase C addresses them (clamped: never stored)
+                    const int64_t ib = row0 + i * 32, col = col0 + j * 32 + l32;
+                    const int64_t cc = col < g.N ? col : g.N - 1;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        int64_t row = ib + (v >> 2) * 8 + lhi * 4 + (v & 3);
+                        prev[v] = g.C[(row < g.M ? row : g.M - 1) * g.ldc + cc];
+                    }
+                }
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    float inner = __builtin_fmaf((float)acc[i][j][v], cs, (float)acc2[v] * cs2);
+                    acc[i][j][v] = __float_as_int(rs[v >> 2][v & 3] * inner + prev[v]);
+                }
+            }
+        }
+
+        // ---- phase B
+        for (int lc = 0; lc < nl; ++lc) {
+            if (!(overlap && lc == 0)) {
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();          // everybody has read what the next loads overwrite
+                asm volatile("" ::: "memory");
+                issue_lora(lc);
+                landed();
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                if (row0 + i * 32 >= g.M) continue;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    if (col0 + j * 32 >= g.N) continue;
+                    f32x16 c = __builtin_bit_cast(f32x16, acc[i][j]);
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {           // 16 columns of r per MFMA
+                        if (lc * 32 + h * 16 >= g.r) continue;
+                        const bf16x8 lb = __builtin_bit_cast(
+                            bf16x8, frag(lora_off + 2 * kLoraParts * PLANE_A, wn * C::WN + j * 32, h * 2 + lhi));
+#pragma unroll
+                        for (int pl = 0; pl < 2 * kLoraParts; ++pl)
+                            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                __builtin_bit_cast(bf16x8, frag(lora_off + pl * PLANE_A, wm * C::WM + i * 32, h * 2 + lhi)),
+                                lb, c, 0, 0, 0);
+                    }
+                    acc[i][j] = __builtin_bit_cast(i32x16, c);
+                }
+            }
+        }
+    }
+
+    // ---- phase C
+    if constexpr (OUT16) {
+        out16_phase();
         return;
     }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        const int64_t ib = row0 + i * 32;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            const int64_t jb = col0 + j * 32, col = jb + l32;
-            if (ib >= g.M || jb >= g.N) continue;
-            float* out = g.C + (ib + lhi * 4) * g.ldc + col;
-            if (ib + 32 <= g.M && jb + 32 <= g.N) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) out[((v >> 2) * 8 + (v & 3)) * g.ldc] = __int_as_float(acc[i][j][v]);
-            } else {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    int64_t row = ib + (v >> 2) * 8 + lhi * 4 + (v & 3);
-                    if (row < g.M && col < g.N) out[((v >> 2) * 8 + (v & 3)) * g.ldc] = __int_as_float(acc[i][j][v]);
-                }
-            }
+            if (row0 + i * 32 >= g.M || col0 + j * 32 >= g.N) continue;
+            store_block(i, j, acc[i][j]);
         }
     }
 }
