@@ -372,31 +372,39 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
     const int lora_off = overlap ? k2_bytes : 0;
     const int64_t row0 = m0 + wm * C::WM, col0 = n0 + wn * C::WN;
 
-    // loader: as in the main loop, one direct load fills 16 rows x 64 bytes; lane -> (row, swizzled 16-byte chunk)
+    // loader: as in the main loop, one direct load fills 16 rows x 64 bytes; lane -> (row, swizzled 16-byte chunk).
+    // A source plane is `nrows` rows, `stride` bytes apart, from the tile's first row (`first`, the same for every
+    // lane: the address is a scalar base plus a 32-bit lane offset); rows past the edge of the matrix repeat the last
+    // valid one (`last`: never stored).
     const int ld_r = lane >> 2, ld_chunk = (lane & 3) ^ ((lane >> 4) & 3);
-    auto fill = [&](int lds_off, int nrows, auto src_of) {
-        for (int q = wave; q < nrows / 16; q += C::NW)
-            dma_load_16<C::DMA_ASM>(src_of(q * 16 + ld_r), dma + lds_off + q * 1024);
+    const int last_a = (int)((g.M - 1 - m0) < (int64_t)(BM - 1) ? (g.M - 1 - m0) : (int64_t)(BM - 1));
+    const int last_b = (int)((g.N - 1 - n0) < (int64_t)(BN - 1) ? (g.N - 1 - n0) : (int64_t)(BN - 1));
+    auto fill = [&](int lds_off, int nrows, const void* first, int last, uint32_t stride, uint32_t col_byte) {
+        for (int q = wave; q < nrows / 16; q += C::NW) {
+            const int local = q * 16 + ld_r;
+            const uint32_t off = (uint32_t)(local < last ? local : last) * stride + col_byte;
+            dma_load_16<C::DMA_ASM>(static_cast<const char*>(first) + off, dma + lds_off + q * 1024);
+        }
     };
-    auto a_row = [&](int local) { int64_t r = m0 + local; return r < g.M ? r : g.M - 1; };   // clamped: never stored
-    auto b_row = [&](int local) { int64_t r = n0 + local; return r < g.N ? r : g.N - 1; };
     auto issue_k2 = [&]() {
         for (int kk = 0; kk < nk; ++kk) {
-            const int off = kk * C::K2_PLANES_BYTES, kb = kk * 64 + ld_chunk * 16;
-            fill(off, BM, [&](int local) { return g.A2 + a_row(local) * g.K2 + kb; });
-            fill(off + PLANE_A, BN, [&](int local) { return g.B2 + b_row(local) * g.K2 + kb; });
+            const int off = kk * C::K2_PLANES_BYTES;
+            const uint32_t kb = (uint32_t)(kk * 64 + ld_chunk * 16);
+            fill(off, BM, g.A2 + m0 * g.K2, last_a, (uint32_t)g.K2, kb);
+            fill(off + PLANE_A, BN, g.B2 + n0 * g.K2, last_b, (uint32_t)g.K2, kb);
         }
     };
     auto issue_lora = [&](int lc) {
         // columns [32 lc, 32 lc + 32) of r; a chunk past r repeats chunk 0 (it is never multiplied)
-        const int pc = lc * 32 + (lc * 32 + ld_chunk * 8 < g.r ? ld_chunk * 8 : 0);
+        const uint32_t pc = (uint32_t)(lc * 32 + (lc * 32 + ld_chunk * 8 < g.r ? ld_chunk * 8 : 0)) * 2;
+        const uint32_t rb = (uint32_t)g.r * 2;
 #pragma unroll
         for (int part = 0; part < kLoraParts; ++part) {
-            const int64_t po = (int64_t)part * g.M * g.r + pc;
-            fill(lora_off + (2 * part) * PLANE_A, BM, [&](int local) { return g.T_hi + po + a_row(local) * g.r; });
-            fill(lora_off + (2 * part + 1) * PLANE_A, BM, [&](int local) { return g.T_lo + po + a_row(local) * g.r; });
+            const int64_t po = ((int64_t)part * g.M + m0) * g.r;
+            fill(lora_off + (2 * part) * PLANE_A, BM, g.T_hi + po, last_a, rb, pc);
+            fill(lora_off + (2 * part + 1) * PLANE_A, BM, g.T_lo + po, last_a, rb, pc);
         }
-        fill(lora_off + 2 * kLoraParts * PLANE_A, BN, [&](int local) { return g.L + b_row(local) * g.r + pc; });
+        fill(lora_off + 2 * kLoraParts * PLANE_A, BN, g.L + n0 * g.r, last_b, rb, pc);
     };
     auto landed = [&]() {
         QUAFF_WAIT_VMCNT(0);
@@ -419,16 +427,21 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
     {
         constexpr int NA = BM / 64, NB = C::BN_PAD / 64;
         for (int q = wave; q < NA + 2 * NB; q += C::NW) {
-            const float* src;
+            const float* first;
+            int local, last;
             if (q < NA) {
-                src = g.row_scale + a_row(q * 64 + lane);
+                first = g.row_scale + m0;
+                local = q * 64 + lane;
+                last = last_a;
             } else {
-                const int qb = q - NA < NB ? q - NA : q - NA - NB;
                 const float* base = q - NA < NB ? g.col_scale : g.col_scale2;
                 if (base == nullptr) continue;
-                src = base + b_row(qb * 64 + lane);
+                first = base + n0;
+                local = (q - NA < NB ? q - NA : q - NA - NB) * 64 + lane;
+                last = last_b;
             }
-            dma_load_4<C::DMA_ASM>(src, dma + C::EPI_LIMIT + q * 256);
+            dma_load_4<C::DMA_ASM>(reinterpret_cast<const char*>(first) + (uint32_t)(local < last ? local : last) * 4,
+                                   dma + C::EPI_LIMIT + q * 256);
         }
     }
     const lds_i8* rs_plane = rd + C::EPI_LIMIT;
