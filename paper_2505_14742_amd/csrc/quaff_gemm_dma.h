@@ -544,6 +544,18 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
         // wavefronts of the SIMD fill the gaps.  The scheduling barrier after each block bounds the live registers.
         constexpr int L_PLANE = 2 * kLoraParts * PLANE_A;
         constexpr int NB = TM * TN;
+        // this lane's column scales (a missing scale is 1 or 0); the pipelined form reads them once for its TN
+        // block columns, ahead of the loop, so that no block waits for them
+        auto read_cs = [&](int j) { return has_cs ? *(const lds_f32*)(cs_plane + (wn * C::WN + j * 32 + l32) * 4) : 1.0f; };
+        auto read_cs2 = [&](int j) { return has_cs2 ? *(const lds_f32*)(cs2_plane + (wn * C::WN + j * 32 + l32) * 4) : 0.0f; };
+        float col_cs[PIPE ? TN : 1], col_cs2[PIPE ? TN : 1];
+        if constexpr (PIPE) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                col_cs[j] = read_cs(j);
+                col_cs2[j] = read_cs2(j);
+            }
+        }
         auto block_k2 = [&](int i, int j, i32x16& acc2) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc2[v] = 0;
@@ -574,9 +586,7 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
         auto block_dequant = [&](int i, int j, const f32x4 (&rs)[4], const i32x16& acc2, f32x16& c, auto add, auto mode) {
             constexpr bool ADD = decltype(add)::value;
             constexpr int MODE = decltype(mode)::value;
-            const int lcol = wn * C::WN + j * 32 + l32;
-            const float cs = MODE >= 1 && has_cs ? *(const lds_f32*)(cs_plane + lcol * 4) : 1.0f;
-            const float cs2 = MODE == 2 || (MODE == 3 && has_cs2) ? *(const lds_f32*)(cs2_plane + lcol * 4) : 0.0f;
+            const float cs = PIPE ? col_cs[PIPE ? j : 0] : read_cs(j), cs2 = PIPE ? col_cs2[PIPE ? j : 0] : read_cs2(j);
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const float a = (float)acc[i][j][v];
