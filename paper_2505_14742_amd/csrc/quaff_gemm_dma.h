@@ -354,11 +354,16 @@ __device__ __forceinline__ void gemm_mainloop_dma128(const int8_t* __restrict__ 
 
 // Epilogue of the fast kernel.  The operands of the short second product (A2, B2) and of the low-rank term (T, L)
 // are first copied into the now idle LDS ring with direct loads - one memory round trip for the whole workgroup
-// instead of one per 32x32 block - in the same 64-byte-row, XOR-swizzled layout as the main loop's stages, then:
-//   phase A  acc2 = A2 B2^T per block (int32, exact); the block becomes  row_scale * (acc * cs + acc2 * cs2)  in fp32
-//   phase B  the low-rank products accumulate onto the fp32 block, 32 columns of r per staging round
+// instead of one per 32x32 block - in the same 64-byte-row, XOR-swizzled layout as the main loop's stages.
+// A whole tile whose staged operands all fit at once (r <= 32) is then finished block by block: acc2 = A2 B2^T
+// (int32, exact), the block becomes  row_scale * (acc * cs + acc2 * cs2)  in fp32, the low-rank products are added
+// and the block is stored while the next one computes (the epilogue is bound by instruction issue: about five vector
+// instructions and a store per output element).  Edge tiles, r > 32 and operand sets that have to take turns in LDS
+// run the same steps as three phases over all blocks:
+//   phase A  acc2 and the conversion, per block
+//   phase B  the low-rank products accumulate onto the fp32 blocks, 32 columns of r per staging round
 //   phase C  stores (all loads precede all stores: they share one in-order counter)
-// ACCUM adds what C already holds (read in phase A).  The caller guarantees (K2 / 64) * K2_PLANES_BYTES <= EPI_LIMIT.
+// ACCUM adds what C already holds.  The caller guarantees (K2 / 64) * K2_PLANES_BYTES <= EPI_LIMIT.
 template <class C, bool ACCUM, bool OUT16 = false>
 __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (&acc)[C::TM][C::TN],
                                                      lds_i8* __restrict__ dma, const lds_i8* __restrict__ rd,
@@ -556,10 +561,14 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
                 col_cs2[j] = read_cs2(j);
             }
         }
+        // acc2 = A2 B2^T of the block, nk >= 1 (the first MFMA takes a constant zero as its addend: no register clearing)
         auto block_k2 = [&](int i, int j, i32x16& acc2) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc2[v] = 0;
-            for (int kk = 0; kk < nk; ++kk) {
+            const i32x16 zero = {};
+            acc2 = __builtin_amdgcn_mfma_i32_32x32x32_i8(frag(0, wm * C::WM + i * 32, lhi),
+                                                         frag(PLANE_A, wn * C::WN + j * 32, lhi), zero, 0, 0, 0);
+            acc2 = __builtin_amdgcn_mfma_i32_32x32x32_i8(frag(0, wm * C::WM + i * 32, 2 + lhi),
+                                                         frag(PLANE_A, wn * C::WN + j * 32, 2 + lhi), acc2, 0, 0, 0);
+            for (int kk = 1; kk < nk; ++kk) {
                 const int off = kk * C::K2_PLANES_BYTES;
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks)
@@ -568,17 +577,25 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
                                                                  acc2, 0, 0, 0);
             }
         };
-        auto block_lora = [&](int i, int j, f32x16& c) {   // c += T L^T
-            if (nl == 0) return;
+        // c (+)= T L^T of the block; FROM_ZERO: c is the product alone (r >= 16: the first MFMA's addend is a constant)
+        auto block_lora = [&](int i, int j, f32x16& c, auto from_zero) {
+            constexpr bool FROM_ZERO = decltype(from_zero)::value;
+            if (!FROM_ZERO && nl == 0) return;
 #pragma unroll
             for (int h = 0; h < 2; ++h) {           // 16 columns of r per MFMA
-                if (h * 16 >= g.r) continue;
+                if (h > 0 && h * 16 >= g.r) continue;
                 const bf16x8 lb = __builtin_bit_cast(bf16x8, frag(lora_off + L_PLANE, wn * C::WN + j * 32, h * 2 + lhi));
 #pragma unroll
-                for (int pl = 0; pl < 2 * kLoraParts; ++pl)
-                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        __builtin_bit_cast(bf16x8, frag(lora_off + pl * PLANE_A, wm * C::WM + i * 32, h * 2 + lhi)), lb,
-                        c, 0, 0, 0);
+                for (int pl = 0; pl < 2 * kLoraParts; ++pl) {
+                    const bf16x8 tf =
+                        __builtin_bit_cast(bf16x8, frag(lora_off + pl * PLANE_A, wm * C::WM + i * 32, h * 2 + lhi));
+                    if (FROM_ZERO && h == 0 && pl == 0) {
+                        const f32x16 zero = {};
+                        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf, lb, zero, 0, 0, 0);
+                    } else {
+                        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf, lb, c, 0, 0, 0);
+                    }
+                }
             }
         };
         // c = row_scale * (acc * cs + acc2 * cs2) [+ c];  MODE 2: both column scales, 1: cs only, 0: neither,
@@ -611,14 +628,24 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
         i32x16 acc2[PIPE ? 2 : 1];
         f32x16 low[PIPE ? 2 : 1];
         f32x4 rs[4];   // this lane's 16 output rows of a block are 4 runs of 4 consecutive rows
-        auto block_ahead = [&](int b) {   // (blocks past the edge of C read staged rows that exist)
+        auto block_ahead = [&](int b, auto mode) {   // the MFMA work of block b: acc2 and the low-rank product
+            if constexpr (decltype(mode)::value >= 2) {
+                if (nk > 0) {
+                    block_k2(b / TN, b % TN, acc2[b & 1]);
+                } else {                                 // (mode 3 only: multiplied by a zero scale)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) low[b & 1][v] = 0.0f;
-            block_k2(b / TN, b % TN, acc2[b & 1]);
-            block_lora(b / TN, b % TN, low[b & 1]);
+                    for (int v = 0; v < 16; ++v) acc2[b & 1][v] = 0;
+                }
+            }
+            if (nl > 0) {
+                block_lora(b / TN, b % TN, low[b & 1], std::true_type{});
+            } else {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) low[b & 1][v] = 0.0f;
+            }
         };
         auto run = [&](auto mode) {
-            if constexpr (PIPE && !OUT16) block_ahead(0);
+            if constexpr (PIPE && !OUT16) block_ahead(0, mode);
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 const int i = b / TN, j = b % TN;
@@ -629,11 +656,11 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
                 }
                 if constexpr (PIPE && OUT16) {
                     // the arithmetic of the pipelined form, one block at a time (the output strips need the registers)
-                    block_ahead(b);
+                    block_ahead(b, mode);
                     block_dequant(i, j, rs, acc2[b & 1], low[b & 1], std::true_type{}, mode);
                     block_out(i, j, low[b & 1]);
                 } else if constexpr (PIPE) {
-                    if (b + 1 < NB) block_ahead(b + 1);
+                    if (b + 1 < NB) block_ahead(b + 1, mode);
                     f32x16& c = low[b & 1];
                     if constexpr (ACCUM) {
                         f32x16 prev;
@@ -645,10 +672,10 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
                     block_out(i, j, c);
                 } else {
                     f32x16& c = low[0];
-                    if constexpr (decltype(mode)::value >= 2) block_k2(i, j, acc2[0]);
+                    if constexpr (decltype(mode)::value >= 2) block_k2(i, j, acc2[0]);   // mode 2 only here: nk >= 1
                     if constexpr (ACCUM) block_prev(i, j, c);
                     block_dequant(i, j, rs, acc2[0], c, std::integral_constant<bool, ACCUM>{}, mode);
-                    block_lora(i, j, c);
+                    block_lora(i, j, c, std::false_type{});
                     block_out(i, j, c);
                 }
                 __builtin_amdgcn_sched_barrier(0);
