@@ -489,6 +489,18 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
     };
 
     // ---- bf16 form of the last phase (a lambda, so that each path above ends in its own copy of it)
+    // two fp32 blocks values of neighbouring columns -> one word of two bf16 (RNE): lanes 2q and 2q + 1 swap half of
+    // their 16 rows; word p of a lane is row (v >> 2) * 8 + lhi * 4 + (v & 3), v = 2p + (lane & 1), columns 2q, 2q + 1
+    auto pack16 = [&](const i32x16& bits, int p) -> uint32_t {
+        const bool odd = l32 & 1;
+        auto rne = [](int b) { uint32_t u = (uint32_t)b; return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16; };
+        const int even_row = bits[2 * p], odd_row = bits[2 * p + 1];
+        const int mine_keep = odd ? odd_row : even_row;
+        const int mine_send = odd ? even_row : odd_row;
+        const int got = __builtin_amdgcn_mov_dpp(mine_send, 0xB1, 0xF, 0xF, true);   // quad_perm [1, 0, 3, 2]: lane ^ 1
+        const uint32_t lo = rne(odd ? got : mine_keep), hi = rne(odd ? mine_keep : got);
+        return lo | (hi << 16);
+    };
     auto out16_phase = [&]() {
         // bf16 output (round to nearest even).  A 32x32 block is only 64 bytes wide in bf16, so the wavefront's
         // 32 x WN strip is first assembled in a private piece of the idle LDS ring (neighbouring lanes swap half of
@@ -502,7 +514,6 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
         lds_i8* strip_w = dma + wave * STRIP;
         const lds_i8* strip_r = rd + wave * STRIP;
         const bool odd = l32 & 1;
-        auto rne = [](int bits) { uint32_t u = (uint32_t)bits; return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16; };
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int64_t ib = row0 + i * 32;
@@ -511,14 +522,10 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
             for (int j = 0; j < TN; ++j) {
 #pragma unroll
                 for (int p = 0; p < 8; ++p) {
-                    const int mine_keep = acc[i][j][2 * p + (odd ? 1 : 0)];
-                    const int mine_send = acc[i][j][2 * p + (odd ? 0 : 1)];
-                    const int got = __shfl_xor(mine_send, 1, 64);
-                    const uint32_t lo = rne(odd ? got : mine_keep), hi = rne(odd ? mine_keep : got);
+                    const uint32_t word = pack16(acc[i][j], p);
                     const int v = 2 * p + (odd ? 1 : 0);
                     const int row = (v >> 2) * 8 + lhi * 4 + (v & 3);
-                    *(__attribute__((address_space(3))) uint32_t*)(strip_w + row * ROWB + (j * 32 + (l32 & ~1)) * 2) =
-                        lo | (hi << 16);
+                    *(__attribute__((address_space(3))) uint32_t*)(strip_w + row * ROWB + (j * 32 + (l32 & ~1)) * 2) = word;
                 }
             }
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -536,10 +543,11 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
         }
     };
 
-    // (bf16 output: the tile shapes that take their blocks one by one keep the phases below - the same arithmetic,
-    // and the output strips need the registers)
+    // (bf16 output keeps the phases below - the output strips need the registers - with the arithmetic of the form
+    // an fp32 launch takes on the same tile, so that it is that launch's result rounded)
     constexpr bool PIPE = C::NW <= 8 && TM * TN <= 6;
-    if ((!OUT16 || PIPE) && overlap && nl <= 1 && m0 + BM <= g.M && n0 + BN <= g.N) {
+    const bool one_pass = overlap && nl <= 1 && m0 + BM <= g.M && n0 + BN <= g.N;
+    if (!OUT16 && one_pass) {
         // ---- the usual case (a whole tile, every staged operand fits side by side, r <= 32): one pass per 32x32 block, whose
         // stores leave while the next block computes.  Where the registers allow a second block in flight (at most
         // 96 accumulator registers and two wavefronts per SIMD), the correction product and the low-rank product of
@@ -598,8 +606,8 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
                 }
             }
         };
-        // c = row_scale * (acc * cs + acc2 * cs2) [+ c];  MODE 2: both column scales, 1: cs only, 0: neither,
-        // 3: whatever is there (a missing scale is 1 or 0: the bits of the special forms, more instructions)
+        // c = row_scale * (acc * cs + acc2 * cs2) [+ c];  MODE 2: both column scales, 1: cs only, 0: neither
+        // (a missing scale is 1 or 0 in the phases below: the same bits, more instructions)
         auto block_dequant = [&](int i, int j, const f32x4 (&rs)[4], const i32x16& acc2, f32x16& c, auto add, auto mode) {
             constexpr bool ADD = decltype(add)::value;
             constexpr int MODE = decltype(mode)::value;
@@ -607,7 +615,7 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const float a = (float)acc[i][j][v];
-                const float inner = MODE >= 2 ? __builtin_fmaf(a, cs, (float)acc2[v] * cs2) : MODE == 1 ? a * cs : a;
+                const float inner = MODE == 2 ? __builtin_fmaf(a, cs, (float)acc2[v] * cs2) : MODE == 1 ? a * cs : a;
                 const float r = rs[v >> 2][v & 3];
                 c[v] = ADD ? __builtin_fmaf(r, inner, c[v]) : r * inner;
             }
@@ -618,49 +626,31 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
             for (int v = 0; v < 16; ++v)
                 c[v] = *(const gfloat*)(base + (int64_t)((v >> 2) * 8 + (v & 3)) * g.ldc * 4 + store_voff);
         };
-        auto block_out = [&](int i, int j, const f32x16& c) {
-            if constexpr (OUT16) {
-                acc[i][j] = __builtin_bit_cast(i32x16, c);
-            } else {
-                store_block_full(i, j, __builtin_bit_cast(i32x16, c));
-            }
-        };
+        auto block_out = [&](int i, int j, const f32x16& c) { store_block_full(i, j, __builtin_bit_cast(i32x16, c)); };
         i32x16 acc2[PIPE ? 2 : 1];
         f32x16 low[PIPE ? 2 : 1];
         f32x4 rs[4];   // this lane's 16 output rows of a block are 4 runs of 4 consecutive rows
-        auto block_ahead = [&](int b, auto mode) {   // the MFMA work of block b: acc2 and the low-rank product
-            if constexpr (decltype(mode)::value >= 2) {
-                if (nk > 0) {
-                    block_k2(b / TN, b % TN, acc2[b & 1]);
-                } else {                                 // (mode 3 only: multiplied by a zero scale)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) acc2[b & 1][v] = 0;
-                }
-            }
+        auto block_ahead = [&](int b, int buf, auto mode) {   // the MFMA work of block b: acc2 and the low-rank product
+            if constexpr (decltype(mode)::value == 2) block_k2(b / TN, b % TN, acc2[buf]);   // (nk >= 1)
             if (nl > 0) {
-                block_lora(b / TN, b % TN, low[b & 1], std::true_type{});
+                block_lora(b / TN, b % TN, low[buf], std::true_type{});
             } else {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) low[b & 1][v] = 0.0f;
+                for (int v = 0; v < 16; ++v) low[buf][v] = 0.0f;
             }
         };
         auto run = [&](auto mode) {
-            if constexpr (PIPE && !OUT16) block_ahead(0, mode);
+            if constexpr (PIPE) block_ahead(0, 0, mode);
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 const int i = b / TN, j = b % TN;
-                if (j == 0) {
+                if (j == 0 || !PIPE) {   // (read per block where registers are short)
 #pragma unroll
                     for (int vg = 0; vg < 4; ++vg)
                         rs[vg] = *(const lds_f32x4*)(rs_plane + (wm * C::WM + i * 32 + vg * 8 + lhi * 4) * 4);
                 }
-                if constexpr (PIPE && OUT16) {
-                    // the arithmetic of the pipelined form, one block at a time (the output strips need the registers)
-                    block_ahead(b, mode);
-                    block_dequant(i, j, rs, acc2[b & 1], low[b & 1], std::true_type{}, mode);
-                    block_out(i, j, low[b & 1]);
-                } else if constexpr (PIPE) {
-                    if (b + 1 < NB) block_ahead(b + 1, mode);
+                if constexpr (PIPE) {
+                    if (b + 1 < NB) block_ahead(b + 1, (b + 1) & 1, mode);
                     f32x16& c = low[b & 1];
                     if constexpr (ACCUM) {
                         f32x16 prev;
@@ -672,7 +662,7 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
                     block_out(i, j, c);
                 } else {
                     f32x16& c = low[0];
-                    if constexpr (decltype(mode)::value >= 2) block_k2(i, j, acc2[0]);   // mode 2 only here: nk >= 1
+                    if constexpr (decltype(mode)::value == 2) block_k2(i, j, acc2[0]);   // (nk >= 1)
                     if constexpr (ACCUM) block_prev(i, j, c);
                     block_dequant(i, j, rs, acc2[0], c, std::integral_constant<bool, ACCUM>{}, mode);
                     block_lora(i, j, c, std::false_type{});
@@ -680,15 +670,16 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if constexpr (OUT16) out16_phase();
         };
-        if constexpr (OUT16) run(std::integral_constant<int, 3>{});   // one copy: the strips need the registers
-        else if (has_cs2) run(std::integral_constant<int, 2>{});
+        if (has_cs2) run(std::integral_constant<int, 2>{});
         else if (has_cs) run(std::integral_constant<int, 1>{});
         else run(std::integral_constant<int, 0>{});
         return;
     }
     {
+        // bf16 output of a tile whose fp32 form is the pipelined one-pass form: the low-rank product is summed from
+        // zero and joins  row_scale * inner  in one fused multiply-add (phase A leaves `inner` in the block)
+        const bool low_first = OUT16 && PIPE && one_pass && nl == 1;
         // ---- phase A
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
@@ -730,7 +721,7 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     float inner = __builtin_fmaf((float)acc[i][j][v], cs, (float)acc2[v] * cs2);
-                    acc[i][j][v] = __float_as_int(rs[v >> 2][v & 3] * inner + prev[v]);
+                    acc[i][j][v] = __float_as_int(low_first ? inner : rs[v >> 2][v & 3] * inner + prev[v]);
                 }
             }
         }
@@ -750,7 +741,12 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     if (col0 + j * 32 >= g.N) continue;
-                    f32x16 c = __builtin_bit_cast(f32x16, acc[i][j]);
+                    const f32x16 inner = __builtin_bit_cast(f32x16, acc[i][j]);
+                    f32x16 c = inner;
+                    if (low_first) {
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) c[v] = 0.0f;
+                    }
 #pragma unroll
                     for (int h = 0; h < 2; ++h) {           // 16 columns of r per MFMA
                         if (lc * 32 + h * 16 >= g.r) continue;
@@ -761,6 +757,13 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
                             c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                                 __builtin_bit_cast(bf16x8, frag(lora_off + pl * PLANE_A, wm * C::WM + i * 32, h * 2 + lhi)),
                                 lb, c, 0, 0, 0);
+                    }
+                    if (low_first) {
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            const int row = wm * C::WM + i * 32 + (v >> 2) * 8 + lhi * 4 + (v & 3);
+                            c[v] = __builtin_fmaf(*(const lds_f32*)(rs_plane + row * 4), inner[v], c[v]);
+                        }
                     }
                     acc[i][j] = __builtin_bit_cast(i32x16, c);
                 }
