@@ -14,8 +14,10 @@
 namespace quaff {
 
 // R16 = r / 16 column blocks of T.  L_RC: L is [r x c] (contraction-contiguous) else [c x r].
+// Up to r = 32 the kernel is held to 64 registers (8 wavefronts per SIMD): its 16-wavefront workgroups then fit on
+// a compute unit beside a workgroup of the input-gradient product, which the one-call backward step runs them next to.
 template <int R16, bool L_RC>
-__global__ void __launch_bounds__(64 * kLoraWaves)
+__global__ void __launch_bounds__(64 * kLoraWaves, R16 <= 2 ? 8 : 4)
 lora_down_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx, const uint16_t* __restrict__ L,
                  float scale, uint16_t* __restrict__ T_hi, uint16_t* __restrict__ T_lo, int row_blocks,
                  const uint16_t* __restrict__ tr_src, uint16_t* __restrict__ tr_dst, int64_t tr_rows, int64_t tr_cols) {
