@@ -548,9 +548,9 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
     constexpr bool PIPE = C::NW <= 8 && TM * TN <= 6;
     const bool one_pass = overlap && nl <= 1 && m0 + BM <= g.M && n0 + BN <= g.N;
     if (!OUT16 && one_pass) {
-        // ---- the usual case (a whole tile, every staged operand fits side by side, r <= 32): one pass per 32x32 block, whose
-        // stores leave while the next block computes.  Where the registers allow a second block in flight (at most
-        // 96 accumulator registers and two wavefronts per SIMD), the correction product and the low-rank product of
+        // ---- the usual case (a whole tile, every staged operand fits side by side, r <= 32): one pass per 32x32
+        // block, whose stores leave while the next block computes.  Where the registers allow a second block in
+        // flight (at most 96 accumulator registers and two wavefronts per SIMD), the correction and low-rank products of
         // the next block - the latter accumulated from zero, so that neither depends on the conversion arithmetic -
         // are issued before the vector instructions of this block and run under them.  The other tile shapes take
         // the blocks one by one (correction product, conversion, low-rank product onto the result): there the other
