@@ -299,6 +299,10 @@ EDGE_CASES = [
     EdgeCase("mid_out_n200_r16", 2048, 256, 4096, list(range(0, 250))[:200], 16),
     EdgeCase("mid_out_n130_r64", 2048, 256, 4096, list(range(0, 256, 1))[60:190], 64),
     EdgeCase("mid_in_short_contraction", 2048, 4096, 128, [5, 4000], 16),     # input-gradient product on the 256x128 tile
+    # 2048 x 3072 outputs (the 128x192 tile) with more than two outlier slices: the correction product is a launch of
+    # its own and the main product accumulates onto it in the one-pass epilogue; the second case also has an edge tile
+    EdgeCase("o_shape_n200_accumulate", 2048, 256, 3072, list(range(0, 250))[:200], 16),
+    EdgeCase("o_shape_ragged_n140_accumulate", 2000, 256, 3056, list(range(10, 150)), 32),
 ]
 
 
