@@ -562,21 +562,15 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
         auto read_cs = [&](int j) { return has_cs ? *(const lds_f32*)(cs_plane + (wn * C::WN + j * 32 + l32) * 4) : 1.0f; };
         auto read_cs2 = [&](int j) { return has_cs2 ? *(const lds_f32*)(cs2_plane + (wn * C::WN + j * 32 + l32) * 4) : 0.0f; };
         float col_cs[PIPE ? TN : 1], col_cs2[PIPE ? TN : 1];
-        if constexpr (PIPE) {
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                col_cs[j] = read_cs(j);
-                col_cs2[j] = read_cs2(j);
-            }
-        }
         // acc2 = A2 B2^T of the block, nk >= 1 (the first MFMA takes a constant zero as its addend: no register clearing)
-        auto block_k2 = [&](int i, int j, i32x16& acc2) {
+        // SIMPLE (the pipelined form's straight-line variant): one outlier slice, r = 16 - no loops, no branches
+        auto block_k2 = [&](int i, int j, i32x16& acc2, auto simple) {
             const i32x16 zero = {};
             acc2 = __builtin_amdgcn_mfma_i32_32x32x32_i8(frag(0, wm * C::WM + i * 32, lhi),
                                                          frag(PLANE_A, wn * C::WN + j * 32, lhi), zero, 0, 0, 0);
             acc2 = __builtin_amdgcn_mfma_i32_32x32x32_i8(frag(0, wm * C::WM + i * 32, 2 + lhi),
                                                          frag(PLANE_A, wn * C::WN + j * 32, 2 + lhi), acc2, 0, 0, 0);
-            for (int kk = 1; kk < nk; ++kk) {
+            for (int kk = 1; !decltype(simple)::value && kk < nk; ++kk) {
                 const int off = kk * C::K2_PLANES_BYTES;
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks)
@@ -586,11 +580,12 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
             }
         };
         // c (+)= T L^T of the block; FROM_ZERO: c is the product alone (r >= 16: the first MFMA's addend is a constant)
-        auto block_lora = [&](int i, int j, f32x16& c, auto from_zero) {
+        auto block_lora = [&](int i, int j, f32x16& c, auto from_zero, auto simple) {
             constexpr bool FROM_ZERO = decltype(from_zero)::value;
+            constexpr bool SIMPLE = decltype(simple)::value;
             if (!FROM_ZERO && nl == 0) return;
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {           // 16 columns of r per MFMA
+            for (int h = 0; h < (SIMPLE ? 1 : 2); ++h) {           // 16 columns of r per MFMA
                 if (h > 0 && h * 16 >= g.r) continue;
                 const bf16x8 lb = __builtin_bit_cast(bf16x8, frag(lora_off + L_PLANE, wn * C::WN + j * 32, h * 2 + lhi));
 #pragma unroll
@@ -630,17 +625,26 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
         i32x16 acc2[PIPE ? 2 : 1];
         f32x16 low[PIPE ? 2 : 1];
         f32x4 rs[4];   // this lane's 16 output rows of a block are 4 runs of 4 consecutive rows
-        auto block_ahead = [&](int b, int buf, auto mode) {   // the MFMA work of block b: acc2 and the low-rank product
-            if constexpr (decltype(mode)::value == 2) block_k2(b / TN, b % TN, acc2[buf]);   // (nk >= 1)
-            if (nl > 0) {
-                block_lora(b / TN, b % TN, low[buf], std::true_type{});
+        auto block_ahead = [&](int b, int buf, auto mode, auto simple) {   // the MFMA work of block b
+            if constexpr (decltype(mode)::value == 2) block_k2(b / TN, b % TN, acc2[buf], simple);   // (nk >= 1)
+            if (decltype(simple)::value || nl > 0) {
+                block_lora(b / TN, b % TN, low[buf], std::true_type{}, simple);
             } else {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) low[buf][v] = 0.0f;
             }
         };
-        auto run = [&](auto mode) {
-            if constexpr (PIPE) block_ahead(0, 0, mode);
+        auto run = [&](auto mode, auto simple) {
+            constexpr int MODE = decltype(mode)::value;
+            constexpr bool SIMPLE = decltype(simple)::value;
+            if constexpr (PIPE) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    if constexpr (MODE >= 1) col_cs[j] = read_cs(j);
+                    if constexpr (MODE == 2) col_cs2[j] = read_cs2(j);
+                }
+                block_ahead(0, 0, mode, simple);
+            }
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 const int i = b / TN, j = b % TN;
@@ -650,7 +654,7 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
                         rs[vg] = *(const lds_f32x4*)(rs_plane + (wm * C::WM + i * 32 + vg * 8 + lhi * 4) * 4);
                 }
                 if constexpr (PIPE) {
-                    if (b + 1 < NB) block_ahead(b + 1, (b + 1) & 1, mode);
+                    if (b + 1 < NB) block_ahead(b + 1, (b + 1) & 1, mode, simple);
                     f32x16& c = low[b & 1];
                     if constexpr (ACCUM) {
                         f32x16 prev;
@@ -662,18 +666,40 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
                     block_out(i, j, c);
                 } else {
                     f32x16& c = low[0];
-                    if constexpr (decltype(mode)::value == 2) block_k2(i, j, acc2[0]);   // (nk >= 1)
+                    if constexpr (MODE == 2) block_k2(i, j, acc2[0], std::false_type{});   // (nk >= 1)
                     if constexpr (ACCUM) block_prev(i, j, c);
                     block_dequant(i, j, rs, acc2[0], c, std::integral_constant<bool, ACCUM>{}, mode);
-                    block_lora(i, j, c, std::false_type{});
+                    block_lora(i, j, c, std::false_type{}, std::false_type{});
                     block_out(i, j, c);
+                }
+                if constexpr (PIPE && SIMPLE) {
+                    // Issue order of the straight-line variant: the LDS reads of the next block, a first run of this
+                    // block's vector instructions over their latency, then one MFMA of the next block (each depends
+                    // on the one before) after every further run, the stores last.
+                    if (b + 1 < NB) {
+                        constexpr int NM = (MODE == 2 ? 2 : 0) + 2 * kLoraParts;      // MFMAs of a block
+                        constexpr int NV = 16 * (MODE == 2 ? 5 : MODE == 1 ? 3 : 2) + 16; // vector instructions, about
+                        constexpr int RUN = NV / (NM + 1);
+                        __builtin_amdgcn_sched_group_barrier(0x100, (MODE == 2 ? 4 : 0) + 1 + 2 * kLoraParts, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, RUN, 0);
+#pragma unroll
+                        for (int u = 0; u < NM; ++u) {
+                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                            __builtin_amdgcn_sched_group_barrier(0x002, RUN, 0);
+                        }
+                    }
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
-        if (has_cs2) run(std::integral_constant<int, 2>{});
-        else if (has_cs) run(std::integral_constant<int, 1>{});
-        else run(std::integral_constant<int, 0>{});
+        const bool simple = PIPE && nl == 1 && g.r == 16 && nk <= 1;
+        auto run_mode = [&](auto mode) {
+            if (simple) run(mode, std::true_type{});
+            else run(mode, std::false_type{});
+        };
+        if (has_cs2) run_mode(std::integral_constant<int, 2>{});
+        else if (has_cs) run_mode(std::integral_constant<int, 1>{});
+        else run_mode(std::integral_constant<int, 0>{});
         return;
     }
     {
