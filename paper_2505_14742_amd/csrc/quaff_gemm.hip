@@ -36,7 +36,8 @@ static hipError_t launch_dma(const GemmArgs& g, bool dump, hipStream_t stream) {
     using C = DmaCfg<BM, BN, WGM, WGN, STAGES>;
     int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (int)((g.N + BN - 1) / BN);
     TileMap tm = make_tile_map(tiles_m, tiles_n);
-    dim3 grid((unsigned)(8 * tm.rm * tm.rn)), block(C::NT);
+    dim3 grid(8, (unsigned)tm.rn, (unsigned)tm.rm), block(C::NT);   // x = XCD, (z, y) = tile inside its region
+    if (tm.rn > 65535 || tm.rm > 65535) return hipErrorInvalidValue;
     if (dump) {
         auto k = gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, true, MINB, PAIR, false, false, false, BT>;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);

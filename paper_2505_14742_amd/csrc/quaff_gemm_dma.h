@@ -129,17 +129,18 @@ struct DmaCfg {
 
 // Tile order.  Workgroups are dealt to the eight XCDs round-robin by the hardware and every XCD has its own L2, so
 // the tile grid is cut into XM x XN = 8 rectangular regions, one per XCD: the operand panels an XCD touches are
-// then as few as possible.  Returns false for surplus workgroups of a region that is smaller than the largest one.
+// then as few as possible.  The launch grid is (8, rn, rm): workgroups are numbered x fastest, so blockIdx.x is the
+// XCD and (blockIdx.z, blockIdx.y) the tile inside its region - no integer division in the kernel.  Returns false
+// for surplus workgroups of a region that is smaller than the largest one.
 struct TileMap {
-    int tiles_m, tiles_n, xm, xn, rm, rn;   // region grid xm x xn, region size rm x rn (ceil)
+    int tiles_m, tiles_n, xm, xn, rm, rn;   // region grid xm x xn (powers of two), region size rm x rn (ceil)
+    int xn_log2;
 };
-__device__ __forceinline__ bool tile_of_block(const TileMap& t, int bid, int& tm, int& tn) {
-    const int xcd = bid & 7, local = bid >> 3;
-    const int rx = xcd / t.xn, ry = xcd % t.xn;
-    const int lm = local / t.rn, ln = local % t.rn;
+__device__ __forceinline__ bool tile_of_block(const TileMap& t, int xcd, int ln, int lm, int& tm, int& tn) {
+    const int rx = xcd >> t.xn_log2, ry = xcd & (t.xn - 1);
     tm = rx * t.rm + lm;
     tn = ry * t.rn + ln;
-    return lm < t.rm && tm < t.tiles_m && tn < t.tiles_n;
+    return tm < t.tiles_m && tn < t.tiles_n;
 }
 
 // The main loop.  `dma` and `rd` both point at the LDS ring; they are separate restrict-qualified parameters so that
@@ -821,7 +822,7 @@ gemm_i8_dma_kernel(const GemmArgs g, const TileMap tmap) {
     lds_i8* lds = (lds_i8*)lds_raw;
 
     int tile_m, tile_n;
-    if (!tile_of_block(tmap, blockIdx.x, tile_m, tile_n)) return;
+    if (!tile_of_block(tmap, blockIdx.x, blockIdx.y, blockIdx.z, tile_m, tile_n)) return;
 
     const int tid = threadIdx.x, lane = tid & 63;
     // The wavefront number is uniform; telling the compiler so moves the loader's address selects to scalar code,
@@ -924,7 +925,7 @@ gemm_i8_dma_kernel(const GemmArgs g, const TileMap tmap) {
 
 // host side: choose the XCD region grid for a tile grid
 inline TileMap make_tile_map(int tiles_m, int tiles_n) {
-    TileMap best{tiles_m, tiles_n, 1, 8, tiles_m, (tiles_n + 7) / 8};
+    TileMap best{tiles_m, tiles_n, 1, 8, tiles_m, (tiles_n + 7) / 8, 3};
     long best_cost = -1;
     const int xms[4] = {1, 2, 4, 8};
     for (int xm : xms) {
@@ -932,7 +933,8 @@ inline TileMap make_tile_map(int tiles_m, int tiles_n) {
         int rm = (tiles_m + xm - 1) / xm, rn = (tiles_n + xn - 1) / xn;
         // cost: padded work first (surplus workgroups idle), then operand panels touched per XCD
         long cost = (long)rm * rn * 1000 + rm + rn;
-        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = TileMap{tiles_m, tiles_n, xm, xn, rm, rn}; }
+        const int xn_log2 = xn == 1 ? 0 : xn == 2 ? 1 : xn == 4 ? 2 : 3;
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = TileMap{tiles_m, tiles_n, xm, xn, rm, rn, xn_log2}; }
     }
     return best;
 }
