@@ -135,7 +135,7 @@ int quaff_quant_act(const uint16_t* X, int64_t t, int64_t c, int64_t ldx, const 
  *        (xq_O, what_int, delta_what may be NULL when n_outlier = 0);
  *        X [t x c_in] bf16 (ldx), lora_A [c_in x r] bf16, lora_B [r x c_out] bf16: read only when
  *        lora_rank > 0 (may be NULL otherwise)
- *   out: Y [t x c_out] fp32, leading dimension ldy (c_out <= ldy < 2^28, QUAFF_ERR_SHAPE otherwise)
+ *   out: Y [t x c_out] fp32, leading dimension ldy (c_out <= ldy < 2^27, QUAFF_ERR_SHAPE otherwise)
  */
 int quaff_linear_fwd(const int8_t* Xq, const float* delta_x, const int8_t* xq_O, int64_t t, const void* Wq_packed,
                      const float* delta_w, int64_t c_in, int64_t c_out, const int8_t* what_int,
@@ -184,7 +184,7 @@ int quaff_linear_fwd_acc(const int8_t* Xq, const int8_t* xq_O, int64_t t, const 
  *   acc[i, k] = sum_j Gq[i, j] Wq[k, j]                                        (int32, exact)
  *   dX[i, k] = delta_g[i] * acc[i, k] + lora_scale * sum_p (sum_j dY[i, j] B[p, j]) A[k, p]
  *   in : dY [t x c_out] bf16 (lddy); Wq_packed, delta_w; lora_A [c_in x r], lora_B [r x c_out] bf16
- *   out: dX [t x c_in] fp32, leading dimension lddx (c_in <= lddx < 2^28, QUAFF_ERR_SHAPE otherwise)
+ *   out: dX [t x c_in] fp32, leading dimension lddx (c_in <= lddx < 2^27, QUAFF_ERR_SHAPE otherwise)
  */
 int quaff_linear_bwd_dx(const uint16_t* dY, int64_t t, int64_t lddy, const void* Wq_packed, const float* delta_w,
                         int64_t c_in, int64_t c_out, const uint16_t* lora_A, const uint16_t* lora_B,

@@ -25,7 +25,7 @@ bool dims_ok(int64_t t, int64_t c_in, int64_t c_out) {
 }
 bool rank_ok(int32_t r) { return r == 0 || (r > 0 && r <= 64 && r % 16 == 0); }
 // leading dimension of an output of the products (the store addressing keeps four rows in a 32-bit offset)
-bool out_ld_ok(int64_t ld, int64_t cols) { return ld >= cols && ld < ((int64_t)1 << 28); }
+bool out_ld_ok(int64_t ld, int64_t cols) { return ld >= cols && ld < ((int64_t)1 << 27); }
 
 // the packed weight codes as the B operand of the forward (c_out x c_in) or of the input-gradient product
 void set_weight_operand(quaff::GemmArgs& g, const void* packed, int64_t c_in, bool gradient) {

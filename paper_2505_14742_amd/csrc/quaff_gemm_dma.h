@@ -459,7 +459,7 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
     // fp32 store of one 32x32 block (this lane: 16 rows of one column).  The block's first element is the same for
     // every lane, so the row offsets are scalar: a stored row costs one 64-bit add of a scalar to the lane's address
     // instead of a multiply-add chain per row and lane.
-    const uint32_t store_voff = (uint32_t)(((int64_t)lhi * 4 * g.ldc + l32) * 4);   // ldc < 2^28, checked by the caller
+    const uint32_t store_voff = (uint32_t)(((int64_t)lhi * 4 * g.ldc + l32) * 4);   // ldc < 2^27, checked by the caller
     typedef __attribute__((address_space(1))) char gchar;
     typedef __attribute__((address_space(1))) float gfloat;
     auto block_base = [&](int i, int j) {

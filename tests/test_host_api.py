@@ -85,9 +85,9 @@ def test_argument_errors_are_reported_without_touching_the_device():
     bad_rank = list(args)
     bad_rank[9] = 24
     assert lib.quaff_linear_bwd_dx(*bad_rank, A16, need, None) == q.ERR_SHAPE
-    # leading dimension of dX beyond what the store addressing covers (2^28 elements)
+    # leading dimension of dX beyond what the store addressing covers (2^27 elements)
     huge_ld = list(args)
-    huge_ld[12] = 1 << 28
+    huge_ld[12] = 1 << 27
     assert lib.quaff_linear_bwd_dx(*huge_ld, A16, need, None) == q.ERR_SHAPE
     # gamma outside [0, 1]
     assert lib.quaff_scale_update(A16, 8, 64, 64, A16, 4, A16, A16, 64, C.c_float(1.5), A16, A16, A16, A16, None,
