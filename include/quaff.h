@@ -111,6 +111,23 @@ int quaff_scale_update(const uint16_t* X, int64_t t, int64_t c_in, int64_t ldx, 
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * quaff_scale_update for callers that cannot allocate device memory or carry a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels and the same results bit for
+ * bit, with the scratch of that call (partial column maxima and a copy of the previous scales) in an array of
+ * static device memory inside the library instead of `workspace`: 129 x 1024 floats (516 KiB) per device, held until
+ * the process ends.  n_outlier may be at most quaff_scale_update_static_max_outliers() = 1024 (QUAFF_ERR_SHAPE
+ * beyond).  The call allocates nothing; the array's device address is looked up once per device, at the first call
+ * on that device.  All calls on one device share the array: calls that overlap on one device (different streams,
+ * or different host threads) race on it; calls ordered on one stream do not.  Nothing needs clearing between calls:
+ * every entry that a call reads it has written before.
+ */
+int32_t quaff_scale_update_static_max_outliers(void);
+int quaff_scale_update_static(const uint16_t* X, int64_t t, int64_t c_in, int64_t ldx, const int32_t* O,
+                              int32_t n_outlier, const float* W_O, const float* wmax_O, int64_t c_out, float gamma,
+                              float* s_O, float* colscale, int8_t* what_int, float* delta_what, float* cmax_out,
+                              void* stream);
+
+/*
  * Column scaling and per-token quantization (Eq. 5 then Eq. 1 with one step size per token,
  * App. "Quantization Granularity").
  *   xhat[i, j] = X[i, j] * colscale[j]           (colscale NULL = all ones)

@@ -27,6 +27,9 @@ SIGNATURES = {
     "quaff_prepare_weight": (C.c_int, [_vp, _i64, _i64, _i64, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "quaff_scale_update": (C.c_int, [_vp, _i64, _i64, _i64, _vp, _i32, _vp, _vp, _i64, _f32, _vp, _vp, _vp, _vp, _vp,
                                      _vp, _sz, _vp]),
+    "quaff_scale_update_static_max_outliers": (_i32, []),
+    "quaff_scale_update_static": (C.c_int, [_vp, _i64, _i64, _i64, _vp, _i32, _vp, _vp, _i64, _f32, _vp, _vp, _vp, _vp,
+                                            _vp, _vp]),
     "quaff_quant_act": (C.c_int, [_vp, _i64, _i64, _i64, _vp, _vp, _i32, _vp, _vp, _vp, _vp]),
     "quaff_linear_fwd": (C.c_int, [_vp, _vp, _vp, _i64, _vp, _vp, _i64, _i64, _vp, _vp, _i32, _vp, _i64, _vp, _vp,
                                    _i32, _f32, _vp, _i64, _vp, _sz, _vp]),
@@ -142,6 +145,18 @@ def scale_update(X, O, W_O, wmax_O, c_out, gamma, s_O, colscale, what_int, delta
                                     _ptr(cmax_out), _ptr(workspace),
                                     0 if workspace is None else workspace.numel() * workspace.element_size(),
                                     _stream()))
+
+
+def scale_update_static_max_outliers() -> int:
+    return int(lib().quaff_scale_update_static_max_outliers())
+
+
+def scale_update_static(X, O, W_O, wmax_O, c_out, gamma, s_O, colscale, what_int, delta_what, cmax_out):
+    t, c_in = X.shape
+    n = 0 if O is None else O.numel()
+    _check(lib().quaff_scale_update_static(_ptr(X), t, c_in, X.stride(0), _ptr(O), n, _ptr(W_O), _ptr(wmax_O), c_out,
+                                           float(gamma), _ptr(s_O), _ptr(colscale), _ptr(what_int), _ptr(delta_what),
+                                           _ptr(cmax_out), _stream()))
 
 
 def quant_act(X, colscale, O, Xq, delta, xq_O):

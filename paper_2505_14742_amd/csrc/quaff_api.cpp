@@ -154,6 +154,26 @@ int quaff_scale_update(const uint16_t* X, int64_t t, int64_t c_in, int64_t ldx, 
                                                  static_cast<float*>(workspace), static_cast<hipStream_t>(stream)));
 }
 
+int32_t quaff_scale_update_static_max_outliers(void) { return quaff::scale_update_static_max_outliers(); }
+
+int quaff_scale_update_static(const uint16_t* X, int64_t t, int64_t c_in, int64_t ldx, const int32_t* O,
+                              int32_t n_outlier, const float* W_O, const float* wmax_O, int64_t c_out, float gamma,
+                              float* s_O, float* colscale, int8_t* what_int, float* delta_what, float* cmax_out,
+                              void* stream) {
+    if (n_outlier == 0) return dims_ok(t, c_in, c_out) ? QUAFF_OK : QUAFF_ERR_SHAPE;
+    if (!X || !O || !W_O || !wmax_O || !s_O || !colscale || !what_int || !delta_what) return QUAFF_ERR_NULL;
+    if (!dims_ok(t, c_in, c_out) || n_outlier < 0 || n_outlier > c_in ||
+        n_outlier > quaff::scale_update_static_max_outliers() || ldx < c_in || !(gamma >= 0.0f && gamma <= 1.0f))
+        return QUAFF_ERR_SHAPE;
+    if (!aligned16(X) || !aligned16(what_int) || ldx % 8 != 0) return QUAFF_ERR_ALIGN;
+    float* scratch_ptr = nullptr;
+    int st = hip_status(quaff::scale_update_static_scratch(&scratch_ptr));
+    if (st != QUAFF_OK) return st;
+    return hip_status(quaff::launch_scale_update(X, t, c_in, ldx, O, n_outlier, W_O, wmax_O, c_out, gamma, s_O,
+                                                 colscale, what_int, delta_what, cmax_out, scratch_ptr,
+                                                 static_cast<hipStream_t>(stream)));
+}
+
 int quaff_quant_act(const uint16_t* X, int64_t t, int64_t c, int64_t ldx, const float* colscale, const int32_t* O,
                     int32_t n_outlier, int8_t* Xq, float* delta, int8_t* xq_O, void* stream) {
     if (!X || !Xq || !delta) return QUAFF_ERR_NULL;

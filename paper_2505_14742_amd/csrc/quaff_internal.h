@@ -59,6 +59,10 @@ hipError_t launch_scale_update(const uint16_t* X, int64_t t, int64_t c_in, int64
                                float* colscale, int8_t* what_int, float* delta_what, float* cmax_out, float* ws,
                                hipStream_t stream);
 int scale_update_blocks(int64_t t);   // number of partial-max slabs (workspace sizing)
+// quaff_scale_update_static: device address of this device's static scratch (room for scale_update_blocks slabs of
+// up to scale_update_static_max_outliers() channels, plus the previous scales); looked up once per device
+int scale_update_static_max_outliers();
+hipError_t scale_update_static_scratch(float** ptr);
 
 hipError_t launch_quant_act(const uint16_t* X, int64_t t, int64_t c, int64_t ldx, const float* colscale,
                             const int32_t* O, int32_t n, int8_t* Xq, float* delta, int8_t* xq_O, hipStream_t stream);

@@ -11,8 +11,37 @@
 // Maxima of non-negative floats are taken on their bit patterns (same order as unsigned integers) with LDS
 // atomics, which is exact and independent of the order of arrival.
 #include "quaff_scale_body.h"
+#include <mutex>
 
 namespace quaff {
+
+// Scratch of quaff_scale_update_static (callers that cannot allocate): the partial column maxima [slabs x n] and the
+// copy of the previous scales [n] that the workspace of quaff_scale_update otherwise holds.  One copy per device, held
+// until the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; kernels get the
+// address that call returns.
+constexpr int kStaticMaxOutliers = 1024;
+static __device__ __align__(256) __attribute__((used)) float scratch[(size_t)(kMaxSlabs + 1) * kStaticMaxOutliers];
+
+int scale_update_static_max_outliers() { return kStaticMaxOutliers; }
+
+hipError_t scale_update_static_scratch(float** ptr) {
+    static std::mutex mu;
+    static float* per_device[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!per_device[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // this device's copy of the array
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        per_device[dev] = static_cast<float*>(p);
+    }
+    *ptr = per_device[dev];
+    return hipSuccess;
+}
 
 constexpr int kWhatThreads = 128;   // output channels per workgroup of momentum_what_kernel
 constexpr int kPartBatch = 32;     // partial maxima loaded per thread before the first is used

@@ -95,6 +95,13 @@ def test_argument_errors_are_reported_without_touching_the_device():
     # scale update with an empty outlier set is a legal no-op
     assert lib.quaff_scale_update(None, 8, 64, 64, None, 0, None, None, 64, C.c_float(0.2), None, None, None, None,
                                   None, None, 0, None) == q.OK
+    # static-scratch scale update: same checks as quaff_scale_update, plus its maximum outlier count
+    assert lib.quaff_scale_update_static(A16, 8, 2048, 2048, A16, 1025, A16, A16, 64, C.c_float(0.2), A16, A16, A16,
+                                         A16, None, None) == q.ERR_SHAPE
+    assert lib.quaff_scale_update_static(None, 8, 64, 64, A16, 4, A16, A16, 64, C.c_float(0.2), A16, A16, A16, A16,
+                                         None, None) == q.ERR_NULL
+    assert lib.quaff_scale_update_static(None, 8, 64, 64, None, 0, None, None, 64, C.c_float(0.2), None, None, None,
+                                         None, None, None) == q.OK
     # prepare: workspace check
     assert lib.quaff_prepare_weight(A16, 64, 64, 64, None, 0, A16, A16, None, None, None, A16, 16, None) \
         == q.ERR_WORKSPACE
