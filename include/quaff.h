@@ -22,7 +22,9 @@
  *  - Matrices are row-major.  bf16 values are passed as uint16_t bit patterns.
  *  - c_in and c_out must be multiples of 16; t >= 1; n_outlier >= 0; lora_rank is 0 or a multiple of 16
  *    (at most 64).  Data pointers must be 16-byte aligned and leading dimensions multiples of 8 elements.
- *  - O must be sorted, unique and inside [0, c_in): a documented precondition, not checked on the device.
+ *  - O must be sorted, unique and inside [0, c_in): a precondition of every per-step call, which use its entries
+ *    as column indices without looking at them; quaff_check_outliers verifies a list on the device (O is fixed
+ *    before fine-tuning starts, Sec. 3.3, so once per layer is enough).
  *    Non-finite inputs are outside the contract (no hang, no out-of-bounds access, values unspecified).
  *  - Return value: QUAFF_OK or a negative QUAFF_ERR_* code; nothing has been enqueued when an error is
  *    returned for an argument problem.
@@ -89,6 +91,16 @@ size_t quaff_prepare_workspace_bytes(int64_t c_in, int64_t c_out);
 int quaff_prepare_weight(const float* W, int64_t c_in, int64_t c_out, int64_t ldw, const int32_t* O,
                          int32_t n_outlier, void* Wq_packed, float* delta_w, float* W_O, float* wmax_O,
                          int8_t* Wq_plain, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Validity of an outlier channel set (Sec. 3.3: O is identified once on calibration data and stays fixed during
+ * fine-tuning; Eq. 5 indexes the columns of X and the rows of W with it).  Scans O on the device.
+ *   in : O [n_outlier] int32 (may be NULL when n_outlier = 0), c_in
+ *   out: result, one DEVICE int32: 0 when O is strictly ascending (hence unique) with every entry in [0, c_in);
+ *        otherwise 1 + k for the first position k whose entry is out of range or not above its predecessor.
+ * An empty list is valid.  The call only enqueues the scan; read *result after synchronizing with `stream`.
+ */
+int quaff_check_outliers(const int32_t* O, int32_t n_outlier, int64_t c_in, int32_t* result, void* stream);
 
 /*
  * Targeted momentum scaling (Eq. 7, Eq. 8) and the dynamic outlier weights (Eq. 5, quantized as in Eq. 9).

@@ -27,6 +27,7 @@ SIGNATURES = {
     "quaff_prepare_weight": (C.c_int, [_vp, _i64, _i64, _i64, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "quaff_scale_update": (C.c_int, [_vp, _i64, _i64, _i64, _vp, _i32, _vp, _vp, _i64, _f32, _vp, _vp, _vp, _vp, _vp,
                                      _vp, _sz, _vp]),
+    "quaff_check_outliers": (C.c_int, [_vp, _i32, _i64, _vp, _vp]),
     "quaff_scale_update_static_max_outliers": (_i32, []),
     "quaff_scale_update_static": (C.c_int, [_vp, _i64, _i64, _i64, _vp, _i32, _vp, _vp, _i64, _f32, _vp, _vp, _vp, _vp,
                                             _vp, _vp]),
@@ -145,6 +146,12 @@ def scale_update(X, O, W_O, wmax_O, c_out, gamma, s_O, colscale, what_int, delta
                                     _ptr(cmax_out), _ptr(workspace),
                                     0 if workspace is None else workspace.numel() * workspace.element_size(),
                                     _stream()))
+
+
+def check_outliers(O, c_in, result):
+    """Enqueue the validity scan of O; `result` is a one-element int32 device tensor (0 = valid, else 1 + position)."""
+    n = 0 if O is None else O.numel()
+    _check(lib().quaff_check_outliers(_ptr(O), n, c_in, _ptr(result), _stream()))
 
 
 def scale_update_static_max_outliers() -> int:

@@ -154,6 +154,13 @@ int quaff_scale_update(const uint16_t* X, int64_t t, int64_t c_in, int64_t ldx, 
                                                  static_cast<float*>(workspace), static_cast<hipStream_t>(stream)));
 }
 
+int quaff_check_outliers(const int32_t* O, int32_t n_outlier, int64_t c_in, int32_t* result, void* stream) {
+    if (!result || (n_outlier > 0 && !O)) return QUAFF_ERR_NULL;
+    if (n_outlier < 0 || c_in < 1 || c_in >= (1 << 20)) return QUAFF_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(O) | reinterpret_cast<uintptr_t>(result)) & 3u) return QUAFF_ERR_ALIGN;
+    return hip_status(quaff::launch_check_outliers(O, n_outlier, c_in, result, static_cast<hipStream_t>(stream)));
+}
+
 int32_t quaff_scale_update_static_max_outliers(void) { return quaff::scale_update_static_max_outliers(); }
 
 int quaff_scale_update_static(const uint16_t* X, int64_t t, int64_t c_in, int64_t ldx, const int32_t* O,

@@ -64,6 +64,8 @@ int scale_update_blocks(int64_t t);   // number of partial-max slabs (workspace 
 int scale_update_static_max_outliers();
 hipError_t scale_update_static_scratch(float** ptr);
 
+hipError_t launch_check_outliers(const int32_t* O, int32_t n, int64_t c_in, int32_t* result, hipStream_t stream);
+
 hipError_t launch_quant_act(const uint16_t* X, int64_t t, int64_t c, int64_t ldx, const float* colscale,
                             const int32_t* O, int32_t n, int8_t* Xq, float* delta, int8_t* xq_O, hipStream_t stream);
 

@@ -208,6 +208,29 @@ momentum_what_wide_kernel(const uint32_t* __restrict__ part, int nslab, int n, i
     }
 }
 
+// Validity of an outlier index list (Sec. 3.3 fixes O before fine-tuning: one check per layer).  One workgroup scans
+// the list; *result = 0 when O is strictly ascending and inside [0, c_in), else 1 + the first offending position.
+__global__ void __launch_bounds__(256)
+check_outliers_kernel(const int32_t* __restrict__ O, int n, int64_t c_in, int32_t* __restrict__ result) {
+    __shared__ int first_bad;
+    if (threadIdx.x == 0) first_bad = 0x7FFFFFFF;
+    __syncthreads();
+    int mine = 0x7FFFFFFF;
+    for (int k = threadIdx.x; k < n; k += 256) {
+        const int64_t v = O[k];
+        const bool bad = v < 0 || v >= c_in || (k > 0 && (int64_t)O[k - 1] >= v);
+        if (bad && k < mine) mine = k;
+    }
+    if (mine != 0x7FFFFFFF) atomicMin(&first_bad, mine);
+    __syncthreads();
+    if (threadIdx.x == 0) *result = first_bad == 0x7FFFFFFF ? 0 : first_bad + 1;
+}
+
+hipError_t launch_check_outliers(const int32_t* O, int32_t n, int64_t c_in, int32_t* result, hipStream_t stream) {
+    hipLaunchKernelGGL(check_outliers_kernel, dim3(1), dim3(256), 0, stream, O, n, c_in, result);
+    return hipGetLastError();
+}
+
 // as many slabs as the rows allow, but no more partial maxima than momentum_what_kernel reduces in one batch
 int scale_update_gather_slabs(int64_t t, int32_t n) {
     int nslab = scale_update_blocks(t);

@@ -95,6 +95,11 @@ def test_argument_errors_are_reported_without_touching_the_device():
     # scale update with an empty outlier set is a legal no-op
     assert lib.quaff_scale_update(None, 8, 64, 64, None, 0, None, None, 64, C.c_float(0.2), None, None, None, None,
                                   None, None, 0, None) == q.OK
+    # outlier check: the result pointer is required, a negative count and a misaligned list are rejected
+    assert lib.quaff_check_outliers(A16, 4, 64, None, None) == q.ERR_NULL
+    assert lib.quaff_check_outliers(None, 4, 64, A16, None) == q.ERR_NULL
+    assert lib.quaff_check_outliers(A16, -1, 64, A16, None) == q.ERR_SHAPE
+    assert lib.quaff_check_outliers(A16 + 2, 4, 64, A16, None) == q.ERR_ALIGN
     # static-scratch scale update: same checks as quaff_scale_update, plus its maximum outlier count
     assert lib.quaff_scale_update_static(A16, 8, 2048, 2048, A16, 1025, A16, A16, 64, C.c_float(0.2), A16, A16, A16,
                                          A16, None, None) == q.ERR_SHAPE
