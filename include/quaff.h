@@ -15,8 +15,9 @@
  *
  * Conventions
  *  - Every data pointer is a DEVICE pointer owned by the caller, valid on the device that is current when
- *    the call is made; the library never frees or keeps them.  Except where stated the library allocates
- *    nothing: scratch comes from the caller's `workspace` (quaff_workspace_bytes tells how much).
+ *    the call is made; the library never frees or keeps them.  The library allocates nothing and creates no
+ *    streams or events (the quaff_microbench_* aids excepted): scratch comes from the caller's `workspace`
+ *    (quaff_workspace_bytes tells how much).
  *  - All work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the default stream) and the
  *    call returns without synchronizing.  Nothing is printed.
  *  - Matrices are row-major.  bf16 values are passed as uint16_t bit patterns.
@@ -255,17 +256,20 @@ int quaff_lora_bwd_weights(const uint16_t* X, int64_t ldx, const uint16_t* dY, i
  * down-projection dY B^T computed once for both (same arguments, same results up to the rounding of the fp32 sums of
  * that down-projection, whose order may differ between the launches).  Needs lora_rank > 0.
  * `workspace` must hold quaff_bwd_step_workspace_bytes(t, c_in, c_out, lora_rank) bytes.
- * The weight gradients do not depend on the input-gradient product and are enqueued on a second stream that the
- * library keeps per device (created at the first call, default priority), forked from and joined back into `stream`
- * with events: towards the caller everything is ordered on `stream` as usual.  If that stream cannot be created the
- * call runs everything on `stream`.  The second stream and its events are shared by all calls on a device: do not
- * issue this call for one device from several host threads at once.
+ * The weight gradients do not depend on the input-gradient product.  When the caller passes a second stream
+ * (`side_stream`, default priority, on the same device) and two events created with timing disabled (`fork_event`,
+ * `join_event`; hipStream_t / hipEvent_t passed as void*), they are enqueued on that stream beside the product: forked
+ * from `stream` after the shared down-projection and joined back into `stream` before the call returns, so that
+ * towards the caller everything is ordered on `stream` as usual, also when a later launch of the call fails.  The
+ * stream and the events belong to the caller (one set per concurrent caller; the library creates and keeps none)
+ * and may be reused by the next call on the same `stream`.  With any of the three NULL everything runs on `stream`.
  */
 size_t quaff_bwd_step_workspace_bytes(int64_t t, int64_t c_in, int64_t c_out, int32_t lora_rank);
 int quaff_linear_bwd_step(const uint16_t* dY, int64_t t, int64_t lddy, const uint16_t* X, int64_t ldx,
                           const void* Wq_packed, const float* delta_w, int64_t c_in, int64_t c_out,
                           const uint16_t* lora_A, const uint16_t* lora_B, int32_t lora_rank, float lora_scale, float* dX,
-                          int64_t lddx, float* dA, float* dB, void* workspace, size_t workspace_bytes, void* stream);
+                          int64_t lddx, float* dA, float* dB, void* workspace, size_t workspace_bytes, void* stream,
+                          void* side_stream, void* fork_event, void* join_event);
 
 /*
  * Variant of the input gradient on the outlier channels (to be called after quaff_linear_bwd_dx on the same dY and

@@ -45,7 +45,7 @@ SIGNATURES = {
     "quaff_lora_bwd_workspace_bytes": (_sz, [_i64, _i64, _i64, _i32]),
     "quaff_bwd_step_workspace_bytes": (_sz, [_i64, _i64, _i64, _i32]),
     "quaff_linear_bwd_step": (C.c_int, [_vp, _i64, _i64, _vp, _i64, _vp, _vp, _i64, _i64, _vp, _vp, _i32, _f32, _vp,
-                                        _i64, _vp, _vp, _vp, _sz, _vp]),
+                                        _i64, _vp, _vp, _vp, _sz, _vp, _vp, _vp, _vp]),
     "quaff_lora_bwd_weights": (C.c_int, [_vp, _i64, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _i32, _f32, _vp, _vp, _vp,
                                          _sz, _vp]),
     "quaff_bwd_dx_outlier_workspace_bytes": (_sz, [_i64, _i64]),
@@ -218,13 +218,31 @@ def bwd_step_workspace_bytes(t, c_in, c_out, lora_rank) -> int:
     return int(lib().quaff_bwd_step_workspace_bytes(t, c_in, c_out, lora_rank))
 
 
-def linear_bwd_step(dY, X, Wq_packed, delta_w, c_in, c_out, lora_A, lora_B, lora_rank, lora_scale, dX, dA, dB, workspace):
+class SideStream:
+    """A second stream and two events (timing disabled) for quaff_linear_bwd_step, owned by the caller."""
+
+    def __init__(self):
+        import torch
+        self.stream = torch.cuda.Stream()
+        self.fork, self.join = torch.cuda.Event(), torch.cuda.Event()
+        for ev in (self.fork, self.join):   # torch creates the underlying event at its first record
+            ev.record(self.stream)
+        self.stream.synchronize()
+
+    def handles(self):
+        return self.stream.cuda_stream, self.fork.cuda_event, self.join.cuda_event
+
+
+def linear_bwd_step(dY, X, Wq_packed, delta_w, c_in, c_out, lora_A, lora_B, lora_rank, lora_scale, dX, dA, dB, workspace,
+                    side=None):
+    """side: a SideStream (the weight gradients then run beside the input-gradient product) or None."""
     t = dY.shape[0]
+    hs, hf, hj = side.handles() if side is not None else (None, None, None)
     _check(lib().quaff_linear_bwd_step(_ptr(dY), t, dY.stride(0), _ptr(X), X.stride(0), _ptr(Wq_packed), _ptr(delta_w),
                                        c_in, c_out, _ptr(lora_A), _ptr(lora_B), lora_rank, float(lora_scale), _ptr(dX),
                                        dX.stride(0), _ptr(dA), _ptr(dB), _ptr(workspace),
                                        0 if workspace is None else workspace.numel() * workspace.element_size(),
-                                       _stream()))
+                                       _stream(), hs, hf, hj))
 
 
 def bwd_dx_outlier_workspace_bytes(t, c_out) -> int:

@@ -2,7 +2,6 @@
 #include "../../include/quaff.h"
 #include "quaff_internal.h"
 #include <functional>
-#include <mutex>
 
 namespace {
 
@@ -404,28 +403,6 @@ int quaff_lora_bwd_weights(const uint16_t* X, int64_t ldx, const uint16_t* dY, i
                                                    reinterpret_cast<float*>(base + w.part_b), dB, t, lora_rank, s));
 }
 
-namespace {
-// A second stream per device for quaff_linear_bwd_step: the LoRA weight gradients (memory-bound, short kernels) do not
-// depend on the input-gradient product (long, MFMA-bound) and run beside it, forked and joined with events so that
-// everything stays ordered on the caller's stream.  Created on first use, default priority, kept for the process.
-struct SideStream { hipStream_t stream = nullptr; hipEvent_t fork = nullptr, join = nullptr; bool ok = false, tried = false; };
-SideStream* side_stream() {
-    static std::mutex mu;
-    static SideStream per_device[64];
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
-    std::lock_guard<std::mutex> lock(mu);
-    SideStream& ss = per_device[dev];
-    if (!ss.tried) {
-        ss.tried = true;
-        ss.ok = hipStreamCreateWithFlags(&ss.stream, hipStreamNonBlocking) == hipSuccess &&
-                hipEventCreateWithFlags(&ss.fork, hipEventDisableTiming) == hipSuccess &&
-                hipEventCreateWithFlags(&ss.join, hipEventDisableTiming) == hipSuccess;
-    }
-    return ss.ok ? &ss : nullptr;
-}
-}  // namespace
-
 size_t quaff_bwd_step_workspace_bytes(int64_t t, int64_t c_in, int64_t c_out, int32_t lora_rank) {
     if (t <= 0 || c_in <= 0 || c_out <= 0 || lora_rank <= 0) return 0;
     return ws_bwd(t, c_out, lora_rank).total + ws_grad(t, c_in, c_out, lora_rank).total + 256;
@@ -434,7 +411,8 @@ size_t quaff_bwd_step_workspace_bytes(int64_t t, int64_t c_in, int64_t c_out, in
 int quaff_linear_bwd_step(const uint16_t* dY, int64_t t, int64_t lddy, const uint16_t* X, int64_t ldx,
                           const void* Wq_packed, const float* delta_w, int64_t c_in, int64_t c_out,
                           const uint16_t* lora_A, const uint16_t* lora_B, int32_t lora_rank, float lora_scale, float* dX,
-                          int64_t lddx, float* dA, float* dB, void* workspace, size_t workspace_bytes, void* stream) {
+                          int64_t lddx, float* dA, float* dB, void* workspace, size_t workspace_bytes, void* stream,
+                          void* side_stream, void* fork_event, void* join_event) {
     if (!X || !dA || !dB) return QUAFF_ERR_NULL;
     if (!rank_ok(lora_rank) || lora_rank == 0 || t <= 0 || c_in <= 0 || c_out <= 0 || ldx < c_in) return QUAFF_ERR_SHAPE;
     const BwdWs wb = ws_bwd(t, c_out, lora_rank);
@@ -461,24 +439,33 @@ int quaff_linear_bwd_step(const uint16_t* dY, int64_t t, int64_t lddy, const uin
                                                        u16(w.p2_hi), u16(w.p2_lo),
                                                        reinterpret_cast<float*>(base + w.part_b), dB, t, lora_rank, gs));
     };
-    SideStream* side = side_stream();
+    // With a second stream and two events from the caller, the weight gradients (short, memory-bound kernels) run
+    // beside the input-gradient product (long, MFMA-bound): forked from `stream` once T1 exists, joined back into it
+    // at the end.  Without them everything runs on `stream`.  The library creates neither streams nor events.
+    const bool use_side = side_stream && fork_event && join_event && side_stream != stream;
+    hipStream_t gs = static_cast<hipStream_t>(side_stream);
+    hipEvent_t ev_fork = static_cast<hipEvent_t>(fork_event), ev_join = static_cast<hipEvent_t>(join_event);
     bool forked = false;
+    int side_status = QUAFF_OK;
     const std::function<int()> fork = [&]() -> int {
-        if (!side) return QUAFF_OK;
-        // the weight gradients start once T1 exists and run beside the input-gradient product
-        int st = hip_status(hipEventRecord(side->fork, s));
+        if (!use_side) return QUAFF_OK;
+        int st = hip_status(hipEventRecord(ev_fork, s));
         if (st != QUAFF_OK) return st;
-        if ((st = hip_status(hipStreamWaitEvent(side->stream, side->fork, 0))) != QUAFF_OK) return st;
+        if ((st = hip_status(hipStreamWaitEvent(gs, ev_fork, 0))) != QUAFF_OK) return st;
         forked = true;
-        if ((st = weight_grads(side->stream)) != QUAFF_OK) return st;
-        return hip_status(hipEventRecord(side->join, side->stream));
+        side_status = weight_grads(gs);   // reported after the join below
+        return QUAFF_OK;
     };
     int st = linear_bwd_dx_impl(dY, t, lddy, Wq_packed, delta_w, c_in, c_out, lora_A, lora_B, lora_rank, lora_scale, dX,
                                 nullptr, lddx, workspace, wb.total, stream, &fork);
     if (forked) {
-        // whatever happened, the caller's stream waits for what was put on the side stream
-        int st2 = hip_status(hipStreamWaitEvent(s, side->join, 0));
-        return st != QUAFF_OK ? st : st2;
+        // Whatever happened after the fork, the caller's stream joins everything that was put on the side stream,
+        // so that the buffers that work reads and writes stay ordered before the caller's next use of them.
+        int st_rec = hip_status(hipEventRecord(ev_join, gs));
+        int st_wait = st_rec == QUAFF_OK ? hip_status(hipStreamWaitEvent(s, ev_join, 0)) : st_rec;
+        if (st != QUAFF_OK) return st;
+        if (side_status != QUAFF_OK) return side_status;
+        return st_wait;
     }
     if (st != QUAFF_OK) return st;
     return weight_grads(s);

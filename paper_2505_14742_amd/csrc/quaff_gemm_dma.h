@@ -9,6 +9,13 @@
 #include "quaff_gemm_kernel.h"
 #include <type_traits>
 
+#ifndef QUAFF_ABL
+#define QUAFF_ABL 0
+#endif
+#ifndef QUAFF_STORE_MODE
+#define QUAFF_STORE_MODE 0
+#endif
+
 namespace quaff {
 
 typedef __attribute__((address_space(3))) int8_t lds_i8;
@@ -335,16 +342,20 @@ __device__ __forceinline__ void gemm_mainloop_dma128(const int8_t* __restrict__ 
         mfmas(fa0, fb0);
         order_reads(false);
         // this stage has been read by everyone after the barrier; the next one must have landed
+#if QUAFF_ABL != 1
         QUAFF_WAIT_VMCNT((NS - 2) * NLOAD);
+#endif
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         // (the compiler orders every LDS read of a region after the direct loads that precede it in the source)
         if constexpr (C::MFMA_FIRST) read_frags(next, 0, fa0, fb0);
+#if QUAFF_ABL != 2
         {
             int t = kt + NS;
             issue(t < KT ? t : KT - 1, s);
         }
+#endif
         if constexpr (!C::MFMA_FIRST) read_frags(next, 0, fa0, fb0);
         mfmas(fa1, fb1);
         order_reads(true);
@@ -470,8 +481,18 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
     auto store_block_full = [&](int i, int j, const i32x16& bits) {
         gchar* base = block_base(i, j);
 #pragma unroll
-        for (int v = 0; v < 16; ++v)
-            *(gfloat*)(base + (int64_t)((v >> 2) * 8 + (v & 3)) * g.ldc * 4 + store_voff) = __int_as_float(bits[v]);
+        for (int v = 0; v < 16; ++v) {
+            gfloat* dst = (gfloat*)(base + (int64_t)((v >> 2) * 8 + (v & 3)) * g.ldc * 4 + store_voff);
+#if QUAFF_STORE_MODE == 1
+            __hip_atomic_store(dst, __int_as_float(bits[v]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+#elif QUAFF_STORE_MODE == 2
+            __builtin_nontemporal_store(__int_as_float(bits[v]), dst);
+#elif QUAFF_STORE_MODE == 3
+            __hip_atomic_store(dst, __int_as_float(bits[v]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#else
+            *dst = __int_as_float(bits[v]);
+#endif
+        }
     };
     auto store_block = [&](int i, int j, const i32x16& bits) {
         const int64_t ib = row0 + i * 32, jb = col0 + j * 32;

@@ -144,7 +144,8 @@ class OracleLayer:
 
 
 def sample_rows(t, every=16, block=256):
-    """Deterministic row subset: every `every`-th row plus the first and last row of every `block`-row block."""
+    """Deterministic row subset: every `every`-th row plus the first and last row of every `block`-row block.  An odd
+    stride walks through every row position of the 32-row blocks and every swizzle slot of the LDS stages."""
     rows = set(range(0, t, every))
     for b in range(0, t, block):
         rows.add(b)

@@ -27,22 +27,28 @@ def _run(W, O, A, B, scale, X, dY, tag):
     dA_two = torch.empty((L.c_in, r), dtype=torch.float32, device=DEV)
     dB_two = torch.empty((r, L.c_out), dtype=torch.float32, device=DEV)
     q.lora_bwd_weights(Xd, Gd, L.A, L.B, r, scale, dA_two, dB_two, ws2)
-    # the one call, on a scribbled workspace and NaN-filled outputs
-    ws = torch.full((q.bwd_step_workspace_bytes(t, L.c_in, L.c_out, r),), 0x5A, dtype=torch.int8, device=DEV)
-    dX = torch.full((t, L.c_in), float("nan"), dtype=torch.float32, device=DEV)
-    dA = torch.full((L.c_in, r), float("nan"), dtype=torch.float32, device=DEV)
-    dB = torch.full((r, L.c_out), float("nan"), dtype=torch.float32, device=DEV)
-    q.linear_bwd_step(Gd, Xd, L.Wq_packed, L.delta_w, L.c_in, L.c_out, L.A, L.B, r, scale, dX, dA, dB, ws)
-    torch.cuda.synchronize()
-    # dX and dB take the same kernels on the same inputs: same bits.  dA uses the down-projection dY B^T that the dX
-    # launch produced, whose fp32 partial sums may be added in another order than the stand-alone one's.
-    assert torch.equal(dX, dX_two), tag + ": dX differs from quaff_linear_bwd_dx"
-    assert torch.equal(dB, dB_two), tag + ": dB differs from quaff_lora_bwd_weights"
     dA_o, dB_o = orc.lora_grads(X, dY, A, B, scale)
-    assert_close_fp32(host(dA), dA_o, tag + " dA vs oracle")
-    assert_close_fp32(host(dB), dB_o, tag + " dB vs oracle")
-    tol = 2e-5 * max(1.0, float(dA_two.abs().max()))
-    assert float((dA - dA_two).abs().max()) <= tol, tag + ": dA differs from quaff_lora_bwd_weights beyond rounding"
+    # the one call, on a scribbled workspace and NaN-filled outputs: everything on the caller's stream, then with the
+    # weight gradients on a second stream of the caller's (used twice in a row: the events are reusable)
+    side = q.SideStream()
+    for how, sd in (("one stream", None), ("side stream", side), ("side stream again", side)):
+        ws = torch.full((q.bwd_step_workspace_bytes(t, L.c_in, L.c_out, r),), 0x5A, dtype=torch.int8, device=DEV)
+        dX = torch.full((t, L.c_in), float("nan"), dtype=torch.float32, device=DEV)
+        dA = torch.full((L.c_in, r), float("nan"), dtype=torch.float32, device=DEV)
+        dB = torch.full((r, L.c_out), float("nan"), dtype=torch.float32, device=DEV)
+        q.linear_bwd_step(Gd, Xd, L.Wq_packed, L.delta_w, L.c_in, L.c_out, L.A, L.B, r, scale, dX, dA, dB, ws, side=sd)
+        # no synchronize here: what follows on the caller's stream must already be ordered after the side stream's work
+        dX_c, dA_c, dB_c = dX.clone(), dA.clone(), dB.clone()
+        torch.cuda.synchronize()
+        tg = "%s (%s)" % (tag, how)
+        # dX and dB take the same kernels on the same inputs: same bits.  dA uses the down-projection dY B^T that the
+        # dX launch produced, whose fp32 partial sums may be added in another order than the stand-alone one's.
+        assert torch.equal(dX_c, dX_two), tg + ": dX differs from quaff_linear_bwd_dx"
+        assert torch.equal(dB_c, dB_two), tg + ": dB differs from quaff_lora_bwd_weights"
+        assert_close_fp32(host(dA_c), dA_o, tg + " dA vs oracle")
+        assert_close_fp32(host(dB_c), dB_o, tg + " dB vs oracle")
+        tol = 2e-5 * max(1.0, float(dA_two.abs().max()))
+        assert float((dA_c - dA_two).abs().max()) <= tol, tg + ": dA differs from quaff_lora_bwd_weights beyond rounding"
 
 
 _EDGE = [i for i, e in enumerate(synth.EDGE_CASES) if e.lora_rank > 0]

@@ -31,11 +31,13 @@ def test_captured_step_replays_bit_exact(one_call_backward):
     dB = torch.zeros((r, L.c_out), dtype=torch.float32, device=DEV)
     bws = torch.empty(q.bwd_step_workspace_bytes(ec.t, L.c_in, L.c_out, r), dtype=torch.int8, device=DEV)
 
+    second = q.SideStream() if one_call_backward else None   # the caller's second stream: fork / join become graph nodes
+
     def step():
         L.fwd_step(Xd, 0.2)
         if one_call_backward:
             q.linear_bwd_step(Gd, Xd, L.Wq_packed, L.delta_w, L.c_in, L.c_out, L.A, L.B, r, L.lora_scale, L.dX, dA, dB,
-                              bws)
+                              bws, side=second)
         else:
             L.linear_bwd_dx(Gd)
 

@@ -40,7 +40,9 @@ def test_config1_all_steps_full_compare():
         check_step(L, R, synth.activations(p, step), None, p.gamma, backward=False, tag="cfg1 step %d" % step)
 
 
-def _run_projection(p, steps, prepare_check=True):
+def _run_projection(p, steps, prepare_check=True, all_rows=True):
+    """all_rows: every element of Y, dX and the accumulators is compared; otherwise the products are compared on a
+    deterministic row subset (the long-sequence workload: a full oracle step takes minutes there)."""
     from tests.gpu_harness import Layer, OracleLayer, check_prepare, check_step, sample_rows
     t0 = time.time()
     W, O = synth.weight(p), synth.outlier_indices(p)
@@ -48,7 +50,7 @@ def _run_projection(p, steps, prepare_check=True):
     L, R = Layer(W, O, A, B, p.lora_scale, p.t), OracleLayer(W, O, A, B, p.lora_scale)
     if prepare_check:
         check_prepare(L, R)
-    rows = sample_rows(p.t)
+    rows = None if all_rows else sample_rows(p.t, every=13)
     for step in steps:
         X = synth.activations(p, step)
         dY = synth.out_grad(p, step) if p.backward else None
@@ -65,7 +67,9 @@ def test_config2_phi3_attention(name):
 
 @pytest.mark.parametrize("name", ["gate_up", "down"])
 def test_config3_phi3_mlp(name):
-    _run_projection(synth.projection(3, name), range(3))
+    """Ten consecutive steps end to end, every element compared (the 50-step chain of the scale update alone is in
+    test_gpu_behaviour.py)."""
+    _run_projection(synth.projection(3, name), range(10))
 
 
 @pytest.mark.parametrize("name", ["q", "o", "gate", "down"])
@@ -75,7 +79,7 @@ def test_config4_llama7b_layer(name):
 
 @pytest.mark.parametrize("name", ["q", "gate", "down"])
 def test_config5_long_sequence(name):
-    _run_projection(synth.projection(5, name), range(1), prepare_check=(name == "q"))
+    _run_projection(synth.projection(5, name), range(1), prepare_check=(name == "q"), all_rows=False)
 
 
 @pytest.mark.parametrize("name", ["o_proj", "down"])

@@ -107,6 +107,11 @@ def test_argument_errors_are_reported_without_touching_the_device():
                                          None, None) == q.ERR_NULL
     assert lib.quaff_scale_update_static(None, 8, 64, 64, None, 0, None, None, 64, C.c_float(0.2), None, None, None,
                                          None, None, None) == q.OK
+    # one-call backward: argument checks come before any use of the optional second stream and its events
+    assert lib.quaff_linear_bwd_step(A16, 8, 64, None, 64, A16, A16, 64, 64, A16, A16, 16, C.c_float(1.0), A16, 64,
+                                     A16, A16, A16, 1 << 30, None, None, None, None) == q.ERR_NULL
+    assert lib.quaff_linear_bwd_step(A16, 8, 64, A16, 64, A16, A16, 64, 64, A16, A16, 16, C.c_float(1.0), A16, 64,
+                                     A16, A16, A16, 16, None, A16, A16, A16) == q.ERR_WORKSPACE
     # prepare: workspace check
     assert lib.quaff_prepare_weight(A16, 64, 64, 64, None, 0, A16, A16, None, None, None, A16, 16, None) \
         == q.ERR_WORKSPACE
