@@ -212,6 +212,12 @@ def kernel_stats(layers, kinds, launches, nsteps, copy_gbs):
             if copy_gbs:
                 kernels[name]["frac_measured_copy_rate"] = round(gbs / copy_gbs, 4)
     what_bytes = sum(4.0 * L["n"] * L["p"].c_out + L["n_pad"] * L["p"].c_out + 4.0 * L["p"].c_out for L in layers)
+    # one-launch forward preparation: X read once, codes + compact outlier codes + steps written, what requantized,
+    # the LoRA factors read and T (hi / lo pair of both parts) and the transposed B written
+    prep_bytes = quant_bytes + what_bytes + sum(
+        (2.0 * L["p"].c_in * L["r"] + 8.0 * L["p"].t * L["r"] + 4.0 * L["p"].c_out * L["r"]) if L["r"] else 0.0
+        for L in layers)
+    hbm("fwd_prep", prep_bytes)
     if "quant_rows+lora_down" in kernels:
         hbm("quant_rows", quant_bytes)
         hbm("quant_rows+lora_down", fused_bytes)

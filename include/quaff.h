@@ -177,8 +177,15 @@ int quaff_linear_fwd(const int8_t* Xq, const float* delta_x, const int8_t* xq_O,
  * One call for the whole forward step of a layer: quaff_scale_update, quaff_quant_act and quaff_linear_fwd with the
  * same arguments, the same results bit for bit and the same side effects (s_O, colscale, what_int, delta_what,
  * cmax_out, Xq, delta_x, xq_O are all written as by the three calls).  Knowing the whole step lets the library
- * run kernels that do not depend on each other in one launch (the outlier-column abs-max next to the LoRA
- * down-projection, both of which only read X); cases that gain nothing run the three calls one after the other.
+ * run it in fewer launches and fewer passes over X: up to 2048 tokens (at most 64 outlier channels, rank 0 or 16)
+ * everything before the product is ONE launch that reads X once; other usual cases take two combined launches;
+ * cases that gain nothing run the three calls one after the other.
+ * The one-launch form contains the only grid-wide dependency of the path (the column maxima of Eq. 8 range over all
+ * tokens): its workgroups announce themselves through a word of `workspace` and wait for each other.  That wait is
+ * bounded (see quaff_debug_grid_wait_ticks); a workgroup that gives up recomputes the maxima from X itself, so the
+ * results are the same whether or not all workgroups are resident at once.  `workspace` is read and written while
+ * the call runs and must not be shared with work that may run at the same time (as for every call here); what an
+ * earlier call left in it does not matter.
  * `workspace` must hold quaff_fwd_step_workspace_bytes(t, c_in, c_out, n_outlier, lora_rank) bytes.
  */
 size_t quaff_fwd_step_workspace_bytes(int64_t t, int64_t c_in, int64_t c_out, int32_t n_outlier, int32_t lora_rank);
@@ -188,6 +195,12 @@ int quaff_linear_fwd_step(const uint16_t* X, int64_t t, int64_t c_in, int64_t ld
                           float* delta_x, int8_t* xq_O, const void* Wq_packed, const float* delta_w,
                           const uint16_t* lora_A, const uint16_t* lora_B, int32_t lora_rank, float lora_scale, float* Y,
                           int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Test aid (not part of the method): bound of the grid-wide wait inside quaff_linear_fwd_step's one-launch form, in
+ * ticks of the device's 100 MHz wall clock (default 5000 = 50 us; process-wide).  ticks >= 0 sets the bound and
+ * returns the previous one, ticks < 0 only returns it.  0 makes every workgroup that is not the last to arrive give
+ * up at once, which exercises the recomputing path with kernels that still finish normally. */
+long long quaff_debug_grid_wait_ticks(long long ticks);
 
 /* quaff_linear_fwd with the result rounded (to nearest even) to bf16 instead of stored as fp32: the output write,
  * which a launch cannot overlap with anything at a few thousand tokens, is halved.  Everything up to the final

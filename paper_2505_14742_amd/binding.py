@@ -57,6 +57,7 @@ SIGNATURES = {
     "quaff_fwd_step_workspace_bytes": (_sz, [_i64, _i64, _i64, _i32, _i32]),
     "quaff_linear_fwd_step": (C.c_int, [_vp, _i64, _i64, _i64, _vp, _i32, _vp, _vp, _i64, _f32, _vp, _vp, _vp, _vp, _vp,
                                         _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _f32, _vp, _i64, _vp, _sz, _vp]),
+    "quaff_debug_grid_wait_ticks": (C.c_longlong, [C.c_longlong]),
     "quaff_profile_enable": (C.c_int, [C.c_int]),
     "quaff_profile_collect": (_i64, []),
     "quaff_profile_launch": (C.c_int, [_i64, C.POINTER(C.c_int), C.POINTER(C.c_float)]),
@@ -287,6 +288,11 @@ def linear_fwd_step(X, O, W_O, wmax_O, c_out, gamma, s_O, colscale, what_int, de
                                        _ptr(Y), Y.stride(0), _ptr(workspace),
                                        0 if workspace is None else workspace.numel() * workspace.element_size(),
                                        _stream()))
+
+
+def debug_grid_wait_ticks(ticks: int) -> int:
+    """Set (ticks >= 0) or read (ticks < 0) the bound of the one-launch forward preparation's grid-wide wait."""
+    return int(lib().quaff_debug_grid_wait_ticks(ticks))
 
 
 def linear_bwd_dx_acc(dY, Wq_packed, delta_w, c_in, c_out, Gq, delta_g, acc):

@@ -1,11 +1,14 @@
 // C ABI of libquaff: argument checking, workspace carving and kernel launches.  No computation happens here.
 #include "../../include/quaff.h"
 #include "quaff_internal.h"
+#include <atomic>
 #include <functional>
 
 namespace {
 
 thread_local int g_last_hip_error = 0;
+// bound of the grid-wide wait of the one-launch forward preparation, in 100 MHz ticks (quaff_debug_grid_wait_ticks)
+std::atomic<long long> g_grid_wait_ticks{5000};
 
 inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -525,7 +528,12 @@ int quaff_calibrate_outliers(const uint16_t* X, int64_t t_total, int64_t c_in, i
 
 size_t quaff_fwd_step_workspace_bytes(int64_t t, int64_t c_in, int64_t c_out, int32_t n_outlier, int32_t lora_rank) {
     if (t <= 0 || c_in <= 0 || c_out <= 0 || n_outlier < 0 || lora_rank < 0) return 0;
-    return ws_scale(t, n_outlier) + ws_fwd(t, c_in, c_out, lora_rank).total + 256;
+    return ws_scale(t, n_outlier) + ws_fwd(t, c_in, c_out, lora_rank).total +
+           quaff::fwd_prep_scratch_bytes(n_outlier < 64 ? n_outlier : 64) + 256;
+}
+
+long long quaff_debug_grid_wait_ticks(long long ticks) {
+    return ticks < 0 ? g_grid_wait_ticks.load() : g_grid_wait_ticks.exchange(ticks);
 }
 
 int quaff_linear_fwd_step(const uint16_t* X, int64_t t, int64_t c_in, int64_t ldx, const int32_t* O, int32_t n_outlier,
@@ -536,17 +544,22 @@ int quaff_linear_fwd_step(const uint16_t* X, int64_t t, int64_t c_in, int64_t ld
                           int64_t ldy, void* workspace, size_t workspace_bytes, void* stream) {
     if (t <= 0 || c_in <= 0 || c_out <= 0 || n_outlier < 0 || !rank_ok(lora_rank)) return QUAFF_ERR_SHAPE;
     const size_t scale_bytes = ws_scale(t, n_outlier);
-    if (!workspace || workspace_bytes < scale_bytes + ws_fwd(t, c_in, c_out, lora_rank).total) return QUAFF_ERR_WORKSPACE;
+    const FwdWs wf = ws_fwd(t, c_in, c_out, lora_rank);
+    const size_t prep_bytes = quaff::fwd_prep_scratch_bytes(n_outlier < 64 ? n_outlier : 64);
+    if (!workspace || workspace_bytes < scale_bytes + wf.total + prep_bytes) return QUAFF_ERR_WORKSPACE;
     if (!aligned16(workspace)) return QUAFF_ERR_ALIGN;
     if (!colscale) return QUAFF_ERR_NULL;
     if (n_outlier > 0 && !xq_O) return QUAFF_ERR_NULL;
     char* base = static_cast<char*>(workspace);
     void* ws_lin = base + scale_bytes;
-    const size_t ws_lin_bytes = workspace_bytes - scale_bytes;
+    const size_t ws_lin_bytes = wf.total;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    // the combined first launch covers the usual case; everything else is the three calls one after the other
-    const bool combined = n_outlier > 0 && n_outlier <= 1024 && (int64_t)n_outlier * 64 < c_in && lora_rank > 0;
-    if (!combined) {
+    // One launch prepares everything the product needs where it can (a few thousand tokens, at most 64 outlier
+    // channels, rank 0 or 16); two combined launches cover the other usual cases; everything else is the three calls
+    // one after the other.
+    const bool fused = quaff::fwd_prep_covers(t, c_in, n_outlier, lora_rank);
+    const bool combined = !fused && n_outlier > 0 && n_outlier <= 1024 && (int64_t)n_outlier * 64 < c_in && lora_rank > 0;
+    if (!fused && !combined) {
         int st = quaff_scale_update(X, t, c_in, ldx, O, n_outlier, W_O, wmax_O, c_out, gamma, s_O, colscale, what_int,
                                     delta_what, cmax_out, workspace, scale_bytes, stream);
         if (st != QUAFF_OK) return st;
@@ -557,26 +570,38 @@ int quaff_linear_fwd_step(const uint16_t* X, int64_t t, int64_t c_in, int64_t ld
                                 stream);
     }
     // argument checks of the three calls (same conditions, same codes)
-    if (!X || !O || !W_O || !wmax_O || !s_O || !what_int || !delta_what || !Xq || !delta_x || !Wq_packed || !delta_w ||
-        !lora_A || !lora_B || !Y)
+    if (!X || !O || !W_O || !wmax_O || !s_O || !what_int || !delta_what || !Xq || !delta_x || !Wq_packed || !delta_w || !Y)
         return QUAFF_ERR_NULL;
+    if (lora_rank > 0 && (!lora_A || !lora_B)) return QUAFF_ERR_NULL;
     if (!dims_ok(t, c_in, c_out) || n_outlier > c_in || ldx < c_in || !out_ld_ok(ldy, c_out) || !(gamma >= 0.0f && gamma <= 1.0f))
         return QUAFF_ERR_SHAPE;
     if (!aligned16(X) || !aligned16(what_int) || !aligned16(Xq) || !aligned16(colscale) || !aligned16(xq_O) ||
-        !aligned16(Wq_packed) || !aligned16(lora_A) || !aligned16(lora_B) || ldx % 8 != 0)
+        !aligned16(Wq_packed) || (lora_rank > 0 && (!aligned16(lora_A) || !aligned16(lora_B))) || ldx % 8 != 0)
         return QUAFF_ERR_ALIGN;
+    char* lin = static_cast<char*>(ws_lin);
+    uint16_t* t_hi = reinterpret_cast<uint16_t*>(lin + wf.t_hi);
+    uint16_t* t_lo = reinterpret_cast<uint16_t*>(lin + wf.t_lo);
+    uint16_t* lt = reinterpret_cast<uint16_t*>(lin + wf.lt);
+    if (fused) {
+        int st = hip_status(quaff::launch_fwd_prep(X, t, c_in, ldx, O, n_outlier, wmax_O, gamma, s_O, colscale, cmax_out,
+                                                   W_O, c_out, what_int, delta_what, Xq, delta_x, xq_O, lora_A, lora_B,
+                                                   lora_rank, lora_scale, t_hi, t_lo, lt,
+                                                   base + scale_bytes + wf.total, g_grid_wait_ticks.load(), s));
+        if (st != QUAFF_OK) return st;
+        quaff::GemmArgs g;
+        st = fwd_common(Xq, delta_x, xq_O, t, Wq_packed, delta_w, c_in, c_out, what_int, delta_what, n_outlier, g);
+        if (st != QUAFF_OK) return st;
+        if (lora_rank > 0) { g.T_hi = t_hi; g.T_lo = t_lo; g.L = lt; g.r = lora_rank; }
+        g.C = Y; g.ldc = ldy;
+        return hip_status(quaff::launch_gemm(g, false, s));
+    }
     float* wsf = static_cast<float*>(workspace);
     const int nslab = quaff::scale_update_gather_slabs(t, n_outlier);
     uint32_t* part = reinterpret_cast<uint32_t*>(wsf);
     float* s_prev = wsf + (int64_t)nslab * n_outlier;
-    FwdWs w = ws_fwd(t, c_in, c_out, lora_rank);
-    char* lin = static_cast<char*>(ws_lin);
-    uint16_t* t_hi = reinterpret_cast<uint16_t*>(lin + w.t_hi);
-    uint16_t* t_lo = reinterpret_cast<uint16_t*>(lin + w.t_lo);
-    uint16_t* lt = reinterpret_cast<uint16_t*>(lin + w.lt);
     int st = hip_status(quaff::launch_colmax_lora(X, t, c_in, ldx, O, n_outlier, part, s_O, s_prev, nslab, lora_A,
                                                   lora_rank, lora_scale, t_hi, t_lo, lora_B, lt, c_out, s,
-                                                  reinterpret_cast<uint16_t*>(lin + w.at)));
+                                                  reinterpret_cast<uint16_t*>(lin + wf.at)));
     if (st != QUAFF_OK) return st;
     // The second combined launch pays off while all its workgroups are resident at once (it runs the quantizer at
     // the requantization role's register budget); long inputs take the two stand-alone kernels.

@@ -39,7 +39,7 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 // ---- optional per-launch timing (see quaff_profile_* in the C ABI) ------------------------------------
-enum KernelKind { K_PREPARE = 0, K_COLMAX, K_MOMENTUM, K_QUANT, K_LORA, K_GEMM, K_LORA_GRAD, K_OUTLIER_GRAD, K_CALIB, K_QUANT_LORA, K_COLMAX_LORA, K_WHAT_QUANT, KERNEL_KINDS };
+enum KernelKind { K_PREPARE = 0, K_COLMAX, K_MOMENTUM, K_QUANT, K_LORA, K_GEMM, K_LORA_GRAD, K_OUTLIER_GRAD, K_CALIB, K_QUANT_LORA, K_COLMAX_LORA, K_WHAT_QUANT, K_FWD_PREP, KERNEL_KINDS };
 class ProfScope {
 public:
     ProfScope(int kind, hipStream_t stream);
@@ -128,6 +128,18 @@ bool launch_what_quant(const uint32_t* part, int nslab, int32_t n, const float* 
                        const int32_t* O, float* s_O, float* colscale, float* cmax_out, const float* W_O, int64_t c_out,
                        int8_t* what_int, float* delta_what, const uint16_t* X, int64_t t, int64_t c, int64_t ldx,
                        int8_t* Xq, float* delta, int8_t* xq_O, hipStream_t stream, hipError_t* err);
+
+// The whole forward preparation (abs-max, momentum, what, quantizer, down-projection, transposed B) in one launch and
+// one pass over X (quaff_fwd_prep.hip).  `scratch` (fwd_prep_scratch_bytes(n) bytes, 256-byte aligned) holds the arrival
+// word of the bounded grid-wide wait and the per-workgroup column maxima; wait_ticks bounds that wait (100 MHz ticks).
+bool fwd_prep_covers(int64_t t, int64_t c_in, int32_t n, int32_t r);
+size_t fwd_prep_scratch_bytes(int32_t n);
+hipError_t launch_fwd_prep(const uint16_t* X, int64_t t, int64_t c, int64_t ldx, const int32_t* O, int32_t n,
+                           const float* wmax_O, float gamma, float* s_O, float* colscale, float* cmax_out,
+                           const float* W_O, int64_t c_out, int8_t* what_int, float* delta_what, int8_t* Xq,
+                           float* delta, int8_t* xq_O, const uint16_t* A, const uint16_t* B, int32_t r, float scale,
+                           uint16_t* T_hi, uint16_t* T_lo, uint16_t* Bt, void* scratch, long long wait_ticks,
+                           hipStream_t stream);
 
 // Packed weight codes: one int8 copy that serves both products.  Element (j, k) of the [c_out x c_in] code matrix
 // sits in a 128-byte line that holds 64 consecutive k of the two rows j & ~1 and j | 1: every 16-byte chunk is

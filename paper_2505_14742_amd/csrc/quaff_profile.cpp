@@ -21,7 +21,7 @@ std::vector<float> g_ms;           // filled by collect()
 constexpr size_t kMaxRecs = 1 << 16;
 const char* kNames[KERNEL_KINDS] = {"prepare_weight", "colmax_outlier", "momentum_what", "quant_rows", "lora_down",
                                     "gemm_i8", "lora_grad", "outlier_grad", "calibrate", "quant_rows+lora_down", "colmax_outlier+lora_down",
-                                    "momentum_what+quant_rows"};
+                                    "momentum_what+quant_rows", "fwd_prep"};
 }  // namespace
 
 ProfScope::ProfScope(int kind, hipStream_t stream) : stream_(stream), idx_(-1) {

@@ -39,14 +39,22 @@ __device__ __forceinline__ void widen_scale(const u32x4& raw, CsPtr cs, int64_t 
     }
 }
 
+// Eight codes of Eq. 1, packed.  code = rne(x * c): the product is rounded once (fp32), then adding 1.5 * 2^23 rounds
+// it to the nearest integer, ties to even, in the same addition - the sum is exact for |product| < 2^22 - and leaves
+// that integer's two's complement in the low mantissa bits, so the low byte is the code.  No clamp is needed for
+// finite inputs: |x| <= m gives |x * fl(127 / m)| < 127.5, which rounds to at most 127 (a non-finite input, outside
+// the contract, yields an unspecified byte).  Three byte permutes assemble four codes into a word.
 __device__ __forceinline__ u32x2 pack_codes(const float (&v)[8], float c) {
     u32x2 out;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-        uint32_t w = 0;
+        uint32_t b[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) w |= (uint32_t)(rtn_code(v[4 * h + u], c) & 0xFF) << (8 * u);
-        out[h] = w;
+        for (int u = 0; u < 4; ++u) b[u] = __float_as_uint(__fadd_rn(__fmul_rn(v[4 * h + u], c), 12582912.0f));
+        // __builtin_amdgcn_perm(hi, lo, sel): result byte i = byte sel[i] of the pair {hi: bytes 4..7, lo: bytes 0..3}
+        const uint32_t lo = __builtin_amdgcn_perm(b[1], b[0], 0x0C0C0400u);   // byte 0 of b0, byte 0 of b1, zero, zero
+        const uint32_t hi = __builtin_amdgcn_perm(b[3], b[2], 0x04000C0Cu);   // zero, zero, byte 0 of b2, byte 0 of b3
+        out[h] = lo | hi;
     }
     return out;
 }

@@ -54,3 +54,31 @@ def test_fwd_step_workloads(cfg, name):
         A = B = None
     _compare(synth.weight(p), synth.outlier_indices(p), A, B, p.lora_scale,
              [synth.activations(p, s) for s in range(2)], p.gamma, "cfg%d %s" % (cfg, name))
+
+
+@pytest.mark.parametrize("case", ["edge_adjacent", "edge_ragged_rows", "cfg2_o_proj", "cfg3_down", "cfg1_single"])
+def test_fwd_step_when_the_grid_wide_wait_gives_up(case):
+    """The one-launch form bounds its wait for the other workgroups' column maxima.  With the bound forced to zero
+    from the host, every workgroup but the last to arrive gives up and recomputes the maxima from X itself: the
+    kernels still finish normally and every result must still be the bits of the three separate calls."""
+    from paper_2505_14742_amd import binding as q
+    if case.startswith("edge_"):
+        idx = [i for i, e in enumerate(synth.EDGE_CASES) if e.name == case[5:]][0]
+        ec = synth.EDGE_CASES[idx]
+        X, dY, W, O, A, B = synth.edge_case_inputs(ec, idx)
+        args = (W, O, A, B, 0.5, [X, X[::-1].copy()], 0.2)
+    else:
+        cfg, name = int(case[3]), case[5:]
+        p = synth.projection(cfg, name)
+        A, B = synth.lora(p)
+        if p.lora_rank == 0:
+            A = B = None
+        args = (synth.weight(p), synth.outlier_indices(p), A, B, p.lora_scale,
+                [synth.activations(p, s) for s in range(2)], p.gamma)
+    prev = q.debug_grid_wait_ticks(0)
+    try:
+        assert q.debug_grid_wait_ticks(-1) == 0
+        _compare(*args, "give-up path " + case)
+    finally:
+        q.debug_grid_wait_ticks(prev)
+    assert q.debug_grid_wait_ticks(-1) == prev

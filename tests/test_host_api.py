@@ -117,6 +117,13 @@ def test_argument_errors_are_reported_without_touching_the_device():
         == q.ERR_WORKSPACE
 
 
+def test_grid_wait_bound_is_a_host_side_setting():
+    prev = q.debug_grid_wait_ticks(-1)
+    assert prev > 0
+    assert q.debug_grid_wait_ticks(123) == prev and q.debug_grid_wait_ticks(-1) == 123
+    assert q.debug_grid_wait_ticks(prev) == 123 and q.debug_grid_wait_ticks(-1) == prev
+
+
 def test_binding_raises_with_status_text():
     with pytest.raises(q.QuaffError) as e:
         q._check(q.ERR_ALIGN)
