@@ -49,14 +49,15 @@ FwdWs ws_fwd(int64_t t, int64_t c_in, int64_t c_out, int32_t r) {
     w.total = off;
     return w;
 }
-struct BwdWs { size_t gq, dg, t_hi, t_lo, total; };
-BwdWs ws_bwd(int64_t t, int64_t c_out, int32_t r) {
+struct BwdWs { size_t gq, dg, t_hi, t_lo, split, total; };
+BwdWs ws_bwd(int64_t t, int64_t c_in, int64_t c_out, int32_t r) {
     BwdWs w{};
     size_t off = 0;
     w.gq = off;   off += align_up((size_t)t * c_out);
     w.dg = off;   off += align_up((size_t)t * 4);
     w.t_hi = off; off += align_up((size_t)quaff::kLoraParts * t * r * 2);
     w.t_lo = off; off += align_up((size_t)quaff::kLoraParts * t * r * 2);
+    w.split = off; off += align_up(quaff::gemm_split_bytes(t, c_in, c_out));   // dX [t x c_in], contraction c_out
     w.total = off;
     return w;
 }
@@ -122,7 +123,7 @@ size_t quaff_prepare_workspace_bytes(int64_t c_in, int64_t c_out) {
 
 size_t quaff_workspace_bytes(int64_t t, int64_t c_in, int64_t c_out, int32_t n_outlier, int32_t lora_rank) {
     if (t <= 0 || c_in <= 0 || c_out <= 0 || n_outlier < 0 || lora_rank < 0) return 0;
-    size_t a = ws_scale(t, n_outlier), b = ws_fwd(t, c_in, c_out, lora_rank).total, c = ws_bwd(t, c_out, lora_rank).total;
+    size_t a = ws_scale(t, n_outlier), b = ws_fwd(t, c_in, c_out, lora_rank).total, c = ws_bwd(t, c_in, c_out, lora_rank).total;
     size_t m = a > b ? a : b;
     return (m > c ? m : c) + 256;
 }
@@ -291,7 +292,7 @@ static int linear_bwd_dx_impl(const uint16_t* dY, int64_t t, int64_t lddy, const
     if (dX16 && (!aligned16(dX16) || lddx % 8 != 0)) return QUAFF_ERR_ALIGN;
     if (lora_rank > 0 && (!lora_A || !lora_B)) return QUAFF_ERR_NULL;
     if (!dims_ok(t, c_in, c_out) || !rank_ok(lora_rank) || lddy < c_out || !out_ld_ok(lddx, c_in)) return QUAFF_ERR_SHAPE;
-    BwdWs w = ws_bwd(t, c_out, lora_rank);
+    BwdWs w = ws_bwd(t, c_in, c_out, lora_rank);
     if (!workspace || workspace_bytes < w.total) return QUAFF_ERR_WORKSPACE;
     if (!aligned16(dY) || !aligned16(Wq_packed) || !aligned16(delta_w) || !aligned16(workspace) || lddy % 8 != 0 ||
         (lora_rank > 0 && (!aligned16(lora_A) || !aligned16(lora_B))))
@@ -329,6 +330,7 @@ static int linear_bwd_dx_impl(const uint16_t* dY, int64_t t, int64_t lddy, const
         if (st != QUAFF_OK) return st;
     }
     g.C = dX; g.C16 = dX16; g.ldc = lddx;
+    if (w.total > w.split) { g.split_scratch = base + w.split; g.split_wait_ticks = g_grid_wait_ticks.load(); }
     // (the one-call backward step forks its weight-gradient work here: the quantizer and the down-projection are
     // enqueued, the long product is not yet)
     if (before_product && (st = (*before_product)()) != QUAFF_OK) return st;
@@ -408,7 +410,7 @@ int quaff_lora_bwd_weights(const uint16_t* X, int64_t ldx, const uint16_t* dY, i
 
 size_t quaff_bwd_step_workspace_bytes(int64_t t, int64_t c_in, int64_t c_out, int32_t lora_rank) {
     if (t <= 0 || c_in <= 0 || c_out <= 0 || lora_rank <= 0) return 0;
-    return ws_bwd(t, c_out, lora_rank).total + ws_grad(t, c_in, c_out, lora_rank).total + 256;
+    return ws_bwd(t, c_in, c_out, lora_rank).total + ws_grad(t, c_in, c_out, lora_rank).total + 256;
 }
 
 int quaff_linear_bwd_step(const uint16_t* dY, int64_t t, int64_t lddy, const uint16_t* X, int64_t ldx,
@@ -418,7 +420,7 @@ int quaff_linear_bwd_step(const uint16_t* dY, int64_t t, int64_t lddy, const uin
                           void* side_stream, void* fork_event, void* join_event) {
     if (!X || !dA || !dB) return QUAFF_ERR_NULL;
     if (!rank_ok(lora_rank) || lora_rank == 0 || t <= 0 || c_in <= 0 || c_out <= 0 || ldx < c_in) return QUAFF_ERR_SHAPE;
-    const BwdWs wb = ws_bwd(t, c_out, lora_rank);
+    const BwdWs wb = ws_bwd(t, c_in, c_out, lora_rank);
     const GradWs w = ws_grad(t, c_in, c_out, lora_rank);
     if (!workspace || workspace_bytes < wb.total + w.total) return QUAFF_ERR_WORKSPACE;
     if (!aligned16(X) || !aligned16(workspace) || ldx % 8 != 0) return QUAFF_ERR_ALIGN;

@@ -31,14 +31,23 @@ static hipError_t launch_generic(const GemmArgs& g, bool dump, hipStream_t strea
 }
 
 // BT: B is read as [K x N] from the packed weight codes (wide-stage main loop only)
-template <int BM, int BN, int WGM, int WGN, int STAGES, int MINB, int PAIR = 0, bool BT = false>
+template <int BM, int BN, int WGM, int WGN, int STAGES, int MINB, int PAIR = 0, bool BT = false, int KSPLIT = 1>
 static hipError_t launch_dma(const GemmArgs& g, bool dump, hipStream_t stream) {
     using C = DmaCfg<BM, BN, WGM, WGN, STAGES>;
     int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (int)((g.N + BN - 1) / BN);
     TileMap tm = make_tile_map(tiles_m, tiles_n);
-    dim3 grid(8, (unsigned)tm.rn, (unsigned)tm.rm), block(C::NT);   // x = XCD, (z, y) = tile inside its region
-    if (tm.rn > 65535 || tm.rm > 65535) return hipErrorInvalidValue;
-    if (dump) {
+    // x = XCD, (z, y) = tile inside its region; a split contraction doubles y (the two halves of a tile are neighbours)
+    dim3 grid(8, (unsigned)tm.rn * KSPLIT, (unsigned)tm.rm), block(C::NT);
+    if (tm.rn * KSPLIT > 65535 || tm.rm > 65535) return hipErrorInvalidValue;
+    if constexpr (KSPLIT == 2) {
+        if (dump || g.C16 || g.accumulate || (int64_t)(g.K2 / 64) * C::K2_PLANES_BYTES > C::EPI_LIMIT)
+            return hipErrorInvalidValue;
+        auto k = gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, false, MINB, PAIR, true, false, false, BT, 2>;
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_ALLOC);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(k, grid, block, C::LDS_ALLOC, stream, g, tm);
+        return hipGetLastError();
+    } else if (dump) {
         auto k = gemm_i8_dma_kernel<BM, BN, WGM, WGN, STAGES, true, MINB, PAIR, false, false, false, BT>;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
         if (e != hipSuccess) return e;
@@ -88,6 +97,25 @@ int choose_tile(int64_t M, int64_t N) {
 
 static hipError_t launch_gemm_one(const GemmArgs& g, bool dump_acc, hipStream_t stream);
 
+// A product whose output is at most 128 tiles of 256 x 192 (a 2048 x 3072 output is exactly 128) with a long
+// contraction runs as two workgroups per tile, each over half of the contraction: 30 % fewer operand bytes per
+// multiply-add than one 128 x 192 tile per compute unit, whose main loop is bound by the delivery of operands from L2
+// into LDS.  The price is one more trip of the output's worth of int32 sums through the L2 (written, read, and
+// written back when the kernel ends): measured on 2048 x 3072 outputs, the split loses at K = 3072, breaks even at
+// K = 9216 (66.7 against 67.2 us) and wins at K = 16384 (103 against 111 us).
+#ifndef QUAFF_SPLIT_MIN_K
+#define QUAFF_SPLIT_MIN_K 12288
+#endif
+static bool split_applies(int64_t M, int64_t N, int64_t K) {
+    const int64_t tiles = ((M + 255) / 256) * ((N + 191) / 192);
+    return K % 256 == 0 && K >= QUAFF_SPLIT_MIN_K && tiles > 64 && tiles <= 128;
+}
+size_t gemm_split_bytes(int64_t M, int64_t N, int64_t K) {
+    if (!split_applies(M, N, K)) return 0;
+    const size_t tiles = (size_t)((M + 255) / 256) * (size_t)((N + 191) / 192);
+    return tiles * 256 + tiles * 512 * 96 * 4;   // two flags per tile in lines of their own, then 96 accumulators of 512 threads
+}
+
 // the direct-to-LDS loader addresses an operand with 32-bit offsets from its tile's first row
 static bool fast_path_ok(const GemmArgs& g) {
     const int64_t lim32 = (int64_t)1 << 32;
@@ -123,6 +151,10 @@ hipError_t launch_gemm(const GemmArgs& g, bool dump_acc, hipStream_t stream) {
 
 hipError_t launch_gemm_one(const GemmArgs& g, bool dump_acc, hipStream_t stream) {
     if (!fast_path_ok(g)) return launch_generic<128, 128, 64, 2, 2>(g, dump_acc, stream);
+    if (g.split_scratch && !dump_acc && !g.C16 && !g.accumulate && g.K2 <= 128 && split_applies(g.M, g.N, g.K)) {
+        if (g.b_layout == kPackedKN) return launch_dma<256, 192, 4, 2, 4, 1, 2, true, 2>(g, false, stream);
+        return launch_dma<256, 192, 4, 2, 4, 1, 2, false, 2>(g, false, stream);
+    }
     if (g.b_layout == kPackedKN) {
         switch (choose_tile(g.M, g.N)) {
             case 0: return launch_dma<256, 256, 2, 4, 4, 1, 2, true>(g, dump_acc, stream);

@@ -9,12 +9,6 @@
 #include "quaff_gemm_kernel.h"
 #include <type_traits>
 
-#ifndef QUAFF_ABL
-#define QUAFF_ABL 0
-#endif
-#ifndef QUAFF_STORE_MODE
-#define QUAFF_STORE_MODE 0
-#endif
 
 namespace quaff {
 
@@ -342,20 +336,16 @@ __device__ __forceinline__ void gemm_mainloop_dma128(const int8_t* __restrict__ 
         mfmas(fa0, fb0);
         order_reads(false);
         // this stage has been read by everyone after the barrier; the next one must have landed
-#if QUAFF_ABL != 1
         QUAFF_WAIT_VMCNT((NS - 2) * NLOAD);
-#endif
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         // (the compiler orders every LDS read of a region after the direct loads that precede it in the source)
         if constexpr (C::MFMA_FIRST) read_frags(next, 0, fa0, fb0);
-#if QUAFF_ABL != 2
         {
             int t = kt + NS;
             issue(t < KT ? t : KT - 1, s);
         }
-#endif
         if constexpr (!C::MFMA_FIRST) read_frags(next, 0, fa0, fb0);
         mfmas(fa1, fb1);
         order_reads(true);
@@ -379,7 +369,10 @@ __device__ __forceinline__ void gemm_mainloop_dma128(const int8_t* __restrict__ 
 template <class C, bool ACCUM, bool OUT16 = false>
 __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (&acc)[C::TM][C::TN],
                                                      lds_i8* __restrict__ dma, const lds_i8* __restrict__ rd,
-                                                     int64_t m0, int64_t n0, int wm, int wn, int wave, int lane) {
+                                                     int64_t m0, int64_t n0, int wm, int wn, int wave, int lane,
+                                                     bool active = true) {
+    // active = false (wavefront-uniform): this wavefront takes part in the staging loads and the barriers but has no
+    // block of its own to finish (split contraction: the partner workgroup finishes it)
     constexpr int TM = C::TM, TN = C::TN, BM = C::BM_, BN = C::BN_;
     constexpr int PLANE_A = BM * 64;
     const int l32 = lane & 31, lhi = lane >> 5;
@@ -483,15 +476,10 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             gfloat* dst = (gfloat*)(base + (int64_t)((v >> 2) * 8 + (v & 3)) * g.ldc * 4 + store_voff);
-#if QUAFF_STORE_MODE == 1
+            // a relaxed system-scope atomic store is a plain store with write-through cache policy: the output
+            // streams to memory while the epilogue runs instead of staying behind as dirty L2 lines that the end
+            // of the kernel has to write back (measured: 1-2 us less per launch)
             __hip_atomic_store(dst, __int_as_float(bits[v]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-#elif QUAFF_STORE_MODE == 2
-            __builtin_nontemporal_store(__int_as_float(bits[v]), dst);
-#elif QUAFF_STORE_MODE == 3
-            __hip_atomic_store(dst, __int_as_float(bits[v]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#else
-            *dst = __int_as_float(bits[v]);
-#endif
         }
     };
     auto store_block = [&](int i, int j, const i32x16& bits) {
@@ -719,6 +707,7 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
             if (simple) run(mode, std::true_type{});
             else run(mode, std::false_type{});
         };
+        if (!active) return;            // (no barrier follows on this path)
         if (has_cs2) run_mode(std::integral_constant<int, 2>{});
         else if (has_cs) run_mode(std::integral_constant<int, 1>{});
         else run_mode(std::integral_constant<int, 0>{});
@@ -731,7 +720,7 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
         // ---- phase A
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            if (row0 + i * 32 >= g.M) continue;
+            if (row0 + i * 32 >= g.M || !active) continue;
             f32x4 rs[4];   // this lane's 16 output rows of the block are 4 runs of 4 consecutive rows
 #pragma unroll
             for (int vg = 0; vg < 4; ++vg)
@@ -785,7 +774,7 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
             }
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                if (row0 + i * 32 >= g.M) continue;
+                if (row0 + i * 32 >= g.M || !active) continue;
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     if (col0 + j * 32 >= g.N) continue;
@@ -828,22 +817,36 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmArgs& g, i32x16 (
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            if (row0 + i * 32 >= g.M || col0 + j * 32 >= g.N) continue;
+            if (row0 + i * 32 >= g.M || col0 + j * 32 >= g.N || !active) continue;
             store_block(i, j, acc[i][j]);
         }
     }
 }
 
+// Contraction split over the two workgroups of a tile (KSPLIT = 2).  The "giver" (second half of the contraction)
+// writes its int32 accumulators, register image by register image, into the exchange buffer and raises the tile's
+// flag; the "taker" (first half) adds them to its own and runs the epilogue: the sums are integers, so the result is
+// the unsplit product bit for bit.  The hand-over relies on the two workgroups sharing an L2, which the launch grid
+// arranges (same XCD) but the hardware does not promise: the giver records the XCD it ran on, and a taker on another
+// one - or one whose bounded wait runs out - computes the second half itself instead.  The flag is exchanged, never
+// just written: whoever finds the other's mark resets the word to zero, so a finished launch always leaves zeros.
+constexpr unsigned long long kSplitFull = 0x5146474956450000ull;        // | XCD of the giver
+constexpr unsigned long long kSplitAbandoned = 0x5146414241440000ull;
+__device__ __forceinline__ unsigned xcc_id() { return __builtin_amdgcn_s_getreg(((4 - 1) << 11) | 20) & 15u; }
+
 template <int BM, int BN, int WGM, int WGN, int STAGES, bool DUMP, int MINB = 1, int PAIR = 0, bool STAGED = false,
-          bool ACCUM = false, bool OUT16 = false, bool BT = false>
+          bool ACCUM = false, bool OUT16 = false, bool BT = false, int KSPLIT = 1>
 __global__ void __launch_bounds__(64 * WGM * WGN, MINB)
 gemm_i8_dma_kernel(const GemmArgs g, const TileMap tmap) {
     using C = DmaCfg<BM, BN, WGM, WGN, STAGES>;
     extern __shared__ __attribute__((aligned(1024))) int8_t lds_raw[];
     lds_i8* lds = (lds_i8*)lds_raw;
+    static_assert(KSPLIT == 1 || (KSPLIT == 2 && PAIR == 2), "the split exists for the wide-stage main loop");
 
     int tile_m, tile_n;
-    if (!tile_of_block(tmap, blockIdx.x, blockIdx.y, blockIdx.z, tile_m, tile_n)) return;
+    // (split: the two workgroups of a tile are neighbours in y, so they carry the same blockIdx.x = XCD)
+    const int kh = KSPLIT == 2 ? (int)(blockIdx.y & 1) : 0;
+    if (!tile_of_block(tmap, blockIdx.x, KSPLIT == 2 ? blockIdx.y >> 1 : blockIdx.y, blockIdx.z, tile_m, tile_n)) return;
 
     const int tid = threadIdx.x, lane = tid & 63;
     // The wavefront number is uniform; telling the compiler so moves the loader's address selects to scalar code,
@@ -899,10 +902,90 @@ gemm_i8_dma_kernel(const GemmArgs g, const TileMap tmap) {
             for (int j = 0; j < C::TN; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) accw[i][j][v] = 0;
-        gemm_mainloop_dma128<C, BT>(g.A, g.B, voffw, (int)(g.K / 128), lds, lds, wave, wm * C::WM * 128 + fragw, b_off,
-                                    b_step, accw);
+        const int KT = (int)(g.K / 128) / KSPLIT;
+        const int a_frag = wm * C::WM * 128 + fragw;
+        gemm_mainloop_dma128<C, BT>(g.A + (int64_t)kh * KT * 128, g.B + kh * KT * b_step, voffw, KT, lds, lds, wave, a_frag,
+                                    b_off, b_step, accw);
+        bool active = true;                                  // does this wavefront finish (dequantise, store) its block
+        if constexpr (KSPLIT == 2) {
+            // Workgroup kh finishes the tile's row half kh: its wavefronts of the other half ("givers") ship their
+            // accumulators to the partner workgroup, its wavefronts of row half kh ("takers") add what the partner's
+            // same-numbered wavefronts ship.  Thread tid of one workgroup writes slot tid, thread tid of the other
+            // reads it: piece q of a thread at [q][tid], so that every store and load covers whole lines.
+            constexpr int NV = C::TM * C::TN * 4;          // 16-byte pieces of a lane's accumulators
+            const int64_t tile_id = (int64_t)tile_m * tmap.tiles_n + tile_n;
+            // (the two flags of a tile sit 128 bytes apart, each in a line of its own)
+            unsigned long long* flags = reinterpret_cast<unsigned long long*>(g.split_scratch) + tile_id * 32;
+            i32x4* xb = reinterpret_cast<i32x4*>(static_cast<char*>(g.split_scratch) +
+                                                 (size_t)tmap.tiles_m * tmap.tiles_n * 256) +
+                        tile_id * NV * C::NT + tid;
+            const bool giver = (wm >= WGM / 2) == (kh == 0);
+            active = !giver;
+            if (giver) {
+#pragma unroll
+                for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < C::TN; ++j)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            xb[((i * C::TN + j) * 4 + q) * C::NT] = (i32x4){accw[i][j][4 * q], accw[i][j][4 * q + 1],
+                                                                             accw[i][j][4 * q + 2], accw[i][j][4 * q + 3]};
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's pieces have reached the L2
+            }
+            __syncthreads();     // all givers of this workgroup have written; nobody reads the ring any more
+            if (tid == 0) {
+                // raise this workgroup's flag ...
+                const unsigned long long old = __hip_atomic_exchange(flags + 16 * kh, kSplitFull | xcc_id(), __ATOMIC_RELAXED,
+                                                                     __HIP_MEMORY_SCOPE_AGENT);
+                if (old == kSplitAbandoned)     // (the partner stopped waiting and does the work itself)
+                    __hip_atomic_store(flags + 16 * kh, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                // ... and wait, for a bounded time, for the partner's
+                unsigned long long* theirs = flags + 16 * (1 - kh);
+                const long long t0 = (long long)wall_clock64();
+                unsigned long long w;
+                int take = 0;
+                for (;;) {
+                    w = __hip_atomic_load(theirs, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if ((w & ~15ull) == kSplitFull) break;
+                    if ((long long)wall_clock64() - t0 >= g.split_wait_ticks) {
+                        w = __hip_atomic_exchange(theirs, kSplitAbandoned, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(2);
+                }
+                if ((w & ~15ull) == kSplitFull) {
+                    take = (unsigned)(w & 15ull) == xcc_id();
+                    if (!take) __hip_atomic_store(theirs, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                *reinterpret_cast<volatile int*>(lds_raw) = take;
+            }
+            __syncthreads();
+            const int take = *reinterpret_cast<volatile int*>(lds_raw);
+            __syncthreads();
+            if (take) {
+                if (active) {
+#pragma unroll
+                    for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < C::TN; ++j)
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) {
+                                const i32x4 v = xb[((i * C::TN + j) * 4 + q) * C::NT];
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) accw[i][j][4 * q + e] += v[e];
+                            }
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                }
+                __syncthreads();                 // all pieces read: the partner's flag goes back to zero
+                if (tid == 0) __hip_atomic_store(flags + 16 * (1 - kh), 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else {
+                // the other half of the contraction, computed here (the givers' sums are not used again)
+                gemm_mainloop_dma128<C, BT>(g.A + (int64_t)(1 - kh) * KT * 128, g.B + (1 - kh) * KT * b_step, voffw, KT,
+                                            lds, lds, wave, a_frag, b_off, b_step, accw);
+            }
+        }
         if constexpr (STAGED && !DUMP)
-            gemm_epilogue_staged<C, ACCUM, OUT16>(g, accw, lds, lds, m0, n0, wm, wn, wave, lane);
+            gemm_epilogue_staged<C, ACCUM, OUT16>(g, accw, lds, lds, m0, n0, wm, wn, wave, lane, active);
         else
             gemm_epilogue<C::TM, C::TN, DUMP>(g, accw, m0 + wm * C::WM, n0 + wn * C::WN, l32, lhi);
         return;

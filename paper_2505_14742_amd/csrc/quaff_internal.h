@@ -177,7 +177,11 @@ struct GemmArgs {
     int32_t accumulate;            // fast kernel only: add the result to what C already holds instead of overwriting it
                                    // (selects a separate kernel instantiation)
     int32_t* acc1; int32_t* acc2;  // int32 dumps (mode 1), dense ld = N
+    // optional scratch for a contraction split over two workgroups per tile (fast kernel; gemm_split_bytes(M, N) bytes,
+    // 256-byte aligned; nullptr = never split) and the bound of the taker's wait in 100 MHz ticks
+    void* split_scratch; long long split_wait_ticks;
 };
+size_t gemm_split_bytes(int64_t M, int64_t N, int64_t K);   // 0 for products that are not split
 hipError_t launch_gemm(const GemmArgs& g, bool dump_acc, hipStream_t stream);
 
 }  // namespace quaff

@@ -19,7 +19,9 @@ CASES = [(300, 512, 384, 0),        # edge tiles in both directions, no correcti
          (2051, 3072, 3072, 31),    # the 128x192 tile's one-pass epilogue plus a ragged row tile
          (515, 1024, 576, 200),     # more than two slices: correction launch + accumulating main launch
          (2048, 256, 9216, 65),     # the 256x288 tile
-         (64, 208, 144, 5)]         # contraction not a multiple of 64: the register-staged kernel
+         (64, 208, 144, 5),         # contraction not a multiple of 64: the register-staged kernel
+         (1280, 3072, 12288, 0)]    # dX contracts over 12288 channels into a 1280 x 3072 output: the contraction is
+                                    # split over two workgroups per tile, which exchange int32 partial sums
 
 
 def _small_ints(seed, stream, shape, lim):
@@ -48,7 +50,8 @@ def test_unit_scales_give_the_integer_products_exactly(t, c_in, c_out, n):
     if n:
         xo[:, :n] = _small_ints(seed, 3, (t, n), 9)
         wh[:, :n] = _small_ints(seed, 4, (c_out, n), 9)
-    want = Xq @ Wi + xo @ wh.T
+    # (float64 products of these small integers are exact and run on the BLAS)
+    want = (Xq.astype(np.float64) @ Wi.astype(np.float64) + xo.astype(np.float64) @ wh.T.astype(np.float64))
     assert np.abs(want).max() < 2 ** 24
     ones_t = torch.ones(t, dtype=torch.float32, device=DEV)
     ones_c = torch.ones(c_out, dtype=torch.float32, device=DEV)
@@ -71,14 +74,24 @@ def test_unit_scales_give_the_integer_products_exactly(t, c_in, c_out, n):
     G = _small_ints(seed, 5, (t, c_out), 7)
     G[:, 1] = 127
     dY_d = torch.from_numpy(synth.f32_to_bf16(G.astype(np.float32).ravel()).reshape(t, c_out).view(np.int16)).to(DEV)
-    want_dx = G @ Wi.T
+    want_dx = G.astype(np.float64) @ Wi.T.astype(np.float64)
     assert np.abs(want_dx).max() < 2 ** 24
     wsb = torch.empty(q.workspace_bytes(t, c_in, c_out, 0, 0), dtype=torch.int8, device=DEV)
     dXbuf = torch.full((t, c_in + 8), float("nan"), dtype=torch.float32, device=DEV)
     dX = dXbuf[:, :c_in]
-    q.linear_bwd_dx(dY_d, Wp, dw, c_in, c_out, None, None, 0, 0.0, dX, wsb)
-    torch.cuda.synchronize()
-    got = dX.cpu().numpy().astype(np.float64)
-    bad = np.argwhere(got != want_dx)
-    assert bad.size == 0, "dX != acc at %s: %r vs %r" % (bad[0], got[tuple(bad[0])], want_dx[tuple(bad[0])])
-    assert torch.isnan(dXbuf[:, c_in:]).all()
+    # the second pass forces every bounded device-side wait to give up at once (a split contraction then computes
+    # its partner's half itself): the kernels still finish and the result is the same
+    for ticks in (None, 0):
+        prev = q.debug_grid_wait_ticks(ticks) if ticks is not None else None
+        try:
+            dXbuf.fill_(float("nan"))
+            q.linear_bwd_dx(dY_d, Wp, dw, c_in, c_out, None, None, 0, 0.0, dX, wsb)
+            torch.cuda.synchronize()
+        finally:
+            if prev is not None:
+                q.debug_grid_wait_ticks(prev)
+        got = dX.cpu().numpy().astype(np.float64)
+        bad = np.argwhere(got != want_dx)
+        assert bad.size == 0, "dX != acc at %s (wait bound %s): %r vs %r" % (
+            bad[0], ticks, got[tuple(bad[0])], want_dx[tuple(bad[0])])
+        assert torch.isnan(dXbuf[:, c_in:]).all()
