@@ -45,7 +45,7 @@ FwdWs ws_fwd(int64_t t, int64_t c_in, int64_t c_out, int32_t r) {
     w.t_hi = off; off += align_up((size_t)quaff::kLoraParts * t * r * 2);
     w.t_lo = off; off += align_up((size_t)quaff::kLoraParts * t * r * 2);
     w.lt = off;   off += align_up((size_t)c_out * r * 2);
-    w.at = off;   off += quaff::lora_prefers_transposed(r) ? align_up((size_t)c_in * r * 2) : 0;   // A^T [r x c_in]
+    w.at = off;   off += quaff::lora_prefers_transposed(r, t) ? align_up((size_t)c_in * r * 2) : 0;   // A^T [r x c_in]
     w.total = off;
     return w;
 }
@@ -81,7 +81,7 @@ GradWs ws_grad(int64_t t, int64_t c_in, int64_t c_out, int32_t r) {
     w.p2_lo = off; off += pbytes;
     w.part_a = off; off += align_up((size_t)nslab_a * r * c_in * 4);
     w.part_b = off; off += align_up((size_t)nslab_b * r * c_out * 4);
-    w.at = off; off += quaff::lora_prefers_transposed(r) ? align_up((size_t)c_in * r * 2) : 0;   // A^T [r x c_in]
+    w.at = off; off += quaff::lora_prefers_transposed(r, t) ? align_up((size_t)c_in * r * 2) : 0;   // A^T [r x c_in]
     w.total = off;
     return w;
 }

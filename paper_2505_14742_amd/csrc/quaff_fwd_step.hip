@@ -13,13 +13,13 @@ colmax_lora_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx
                    const uint16_t* __restrict__ L, float scale, uint16_t* __restrict__ T_hi,
                    uint16_t* __restrict__ T_lo, int row_blocks, int lora_nbx, const uint16_t* __restrict__ tr_src,
                    uint16_t* __restrict__ tr_dst, int64_t tr_rows, int64_t tr_cols) {
-    extern __shared__ uint32_t smax[];   // [n]
+    __shared__ uint32_t wred[16 * kLoraWaves];
     const int lora_blocks = lora_nbx * kLoraParts;
     if ((int)blockIdx.x < lora_blocks)
         lora_down_body<R16, L_RC>(blockIdx.x % lora_nbx, blockIdx.x / lora_nbx, lora_nbx, X, t, c, ldx, L, scale, T_hi,
                                    T_lo, row_blocks, tr_src, tr_dst, tr_rows, tr_cols);
     else
-        colmax_outlier_body<64 * kLoraWaves>(blockIdx.x - lora_blocks, nslab, smax, X, t, ldx, O, n, part, s_O, s_prev);
+        colmax_outlier_body<64 * kLoraWaves>(blockIdx.x - lora_blocks, nslab, wred, X, t, ldx, O, n, part, s_O, s_prev);
 }
 
 // part [nslab x n] and s_prev as launch_scale_update lays them out; A is [c x r], B [r x c_out] -> Bt [c_out x r]
@@ -28,7 +28,7 @@ hipError_t launch_colmax_lora(const uint16_t* X, int64_t t, int64_t c, int64_t l
                               float scale, uint16_t* T_hi, uint16_t* T_lo, const uint16_t* B, uint16_t* Bt,
                               int64_t c_out, hipStream_t stream, uint16_t* At_scratch) {
     ProfScope prof(K_COLMAX_LORA, stream);
-    const bool transposed = At_scratch && lora_prefers_transposed(r);
+    const bool transposed = At_scratch && lora_prefers_transposed(r, t);
     if (transposed) {
         hipError_t e = launch_transpose_bf16(A, c, r, At_scratch, stream);
         if (e != hipSuccess) return e;
@@ -42,11 +42,11 @@ hipError_t launch_colmax_lora(const uint16_t* X, int64_t t, int64_t c, int64_t l
 #define QUAFF_CL(N)                                                                                                   \
     case N:                                                                                                           \
         if (transposed)                                                                                               \
-            hipLaunchKernelGGL((colmax_lora_kernel<N, true>), grid, dim3(64 * kLoraWaves), n * sizeof(uint32_t),      \
+            hipLaunchKernelGGL((colmax_lora_kernel<N, true>), grid, dim3(64 * kLoraWaves), 0,      \
                                stream, X, t, (int)c, ldx, O, n, part, s_O, s_prev, nslab, A, scale, T_hi, T_lo,       \
                                row_blocks, lora_nbx, B, Bt, (int64_t)r, c_out);                                       \
         else                                                                                                          \
-            hipLaunchKernelGGL((colmax_lora_kernel<N, false>), grid, dim3(64 * kLoraWaves), n * sizeof(uint32_t),     \
+            hipLaunchKernelGGL((colmax_lora_kernel<N, false>), grid, dim3(64 * kLoraWaves), 0,     \
                                stream, X, t, (int)c, ldx, O, n, part, s_O, s_prev, nslab, A, scale, T_hi, T_lo,       \
                                row_blocks, lora_nbx, B, Bt, (int64_t)r, c_out);                                       \
         break;

@@ -62,7 +62,7 @@ hipError_t launch_lora_down(const uint16_t* X, int64_t t, int64_t c, int64_t ldx
                             uint16_t* tr_dst, int64_t tr_rows, int64_t tr_cols, hipStream_t stream,
                             uint16_t* Lt_scratch) {
     ProfScope prof(K_LORA, stream);
-    if (!L_is_r_by_c && Lt_scratch && lora_prefers_transposed(r)) {
+    if (!L_is_r_by_c && Lt_scratch && lora_prefers_transposed(r, t)) {
         // a [c x r] factor of rank 32 or more is transposed once (r x c, contraction-contiguous) instead of slice by
         // slice through LDS inside the product: one small launch more, a several times faster product
         hipError_t e = launch_transpose_bf16(L, c, r, Lt_scratch, stream);

@@ -3,13 +3,14 @@
 //
 // Two launches:
 //   colmax_outlier_kernel   partial column maxima of |X[:, O]| per slab of rows (a strided 2-byte gather: the
-//                           traffic is one DRAM sector per (row, outlier) whatever the kernel does), and a copy
+//                           traffic is one DRAM sector per (row, outlier) whatever the kernel does; register maxima
+//                           combined with wavefront shuffles), and a copy
 //                           of the previous scales so that the in-place update below has no read/write race;
 //   momentum_what_kernel    every block reduces the partial maxima and evaluates Eq. 8 / Eq. 7 for all outlier
 //                           channels (a few hundred flops, cheaper than another launch); block 0 publishes s,
 //                           1/s and cmax; then each thread requantizes one output channel of what.
-// Maxima of non-negative floats are taken on their bit patterns (same order as unsigned integers) with LDS
-// atomics, which is exact and independent of the order of arrival.
+// Maxima of non-negative floats are taken on their bit patterns (same order as unsigned integers), which is exact
+// and independent of the order in which they are combined.
 #include "quaff_scale_body.h"
 #include <mutex>
 
@@ -54,8 +55,8 @@ int scale_update_blocks(int64_t t) {
 __global__ void __launch_bounds__(256)
 colmax_outlier_kernel(const uint16_t* __restrict__ X, int64_t t, int64_t ldx, const int32_t* __restrict__ O, int n,
                       uint32_t* __restrict__ part, const float* __restrict__ s_O, float* __restrict__ s_prev) {
-    extern __shared__ uint32_t smax[];   // [n]
-    colmax_outlier_body<256>(blockIdx.x, gridDim.x, smax, X, t, ldx, O, n, part, s_O, s_prev);
+    __shared__ uint32_t wred[16 * 256 / 64];
+    colmax_outlier_body<256>(blockIdx.x, gridDim.x, wred, X, t, ldx, O, n, part, s_O, s_prev);
 }
 
 __global__ void __launch_bounds__(kWhatThreads)
@@ -267,7 +268,7 @@ hipError_t launch_scale_update(const uint16_t* X, int64_t t, int64_t c_in, int64
     float* s_prev = ws + (int64_t)nslab * n;            // [n]
     {
         ProfScope prof(K_COLMAX, stream);
-        hipLaunchKernelGGL(colmax_outlier_kernel, dim3(nslab), dim3(256), n * sizeof(uint32_t), stream, X, t, ldx, O,
+        hipLaunchKernelGGL(colmax_outlier_kernel, dim3(nslab), dim3(256), 0, stream, X, t, ldx, O,
                            n, part, s_O, s_prev);
     }
     return launch_momentum(part, nslab, n, n_pad, wmax_O, s_prev, gamma, O, s_O, colscale, cmax_out, W_O, c_out,

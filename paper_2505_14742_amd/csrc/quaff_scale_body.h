@@ -8,38 +8,56 @@ namespace quaff {
 constexpr int kRowsPerSlab = 16;
 constexpr int kMaxSlabs = 128;
 
-// part[slab][k] = max over the slab's rows of |X[row, O_k]|; slab s owns row groups s, s + nslab, ...
-// Work of workgroup `block` of `nslab` (all NT threads take part); smax is n words of LDS.
+// part[slab][k] = max over the slab's rows of |X[row, O_k]|; slab s owns the 16-row groups s, s + nslab, ...
+// Work of workgroup `block` of `nslab` (all NT threads take part).  Sixteen outlier columns are handled per pass:
+// thread (slot = tid / 16, kk = tid % 16) walks rows slot, slot + NT / 16, ... of the slab's groups for column kk of the
+// pass - sixteen neighbouring lanes read sixteen (often neighbouring) columns of one row - and keeps a running maximum
+// in a register, four gathers in flight.  The maxima of a wavefront's four row slots are combined with wavefront
+// shuffles and the wavefronts' results through a small LDS array (plain stores, one barrier): no atomics.
+// wred is 16 * NT / 64 words of LDS.
 template <int NT>
-__device__ __forceinline__ void colmax_outlier_body(int block, int nslab, uint32_t* smax, const uint16_t* __restrict__ X,
+__device__ __forceinline__ void colmax_outlier_body(int block, int nslab, uint32_t* wred, const uint16_t* __restrict__ X,
                                                     int64_t t, int64_t ldx, const int32_t* __restrict__ O, int n,
                                                     uint32_t* __restrict__ part, const float* __restrict__ s_O,
                                                     float* __restrict__ s_prev) {
-    for (int k = threadIdx.x; k < n; k += NT) smax[k] = 0u;
+    constexpr int SLOTS = NT / 16, NWAVE = NT / 64;
+    static_assert(SLOTS % kRowsPerSlab == 0, "the row slots of a pass cover whole 16-row groups");
     if (block == 0)
         for (int k = threadIdx.x; k < n; k += NT) s_prev[k] = s_O[k];
-    __syncthreads();
-    const int per_group = kRowsPerSlab * n;
-    for (int64_t r0 = (int64_t)block * kRowsPerSlab; r0 < t; r0 += (int64_t)nslab * kRowsPerSlab) {
-        for (int e0 = threadIdx.x; e0 < per_group; e0 += 4 * NT) {   // four independent gathers in flight per thread
-            uint32_t mag[4];
-            int kk[4];
+    const int kk = threadIdx.x & 15, slot = threadIdx.x >> 4;
+    // row of this thread in its first pass over the slab's groups, and the distance between passes: the slab's
+    // groups are 16 rows every nslab * 16 rows; the SLOTS row slots of a pass cover SLOTS / 16 of them
+    constexpr int GPP = SLOTS / kRowsPerSlab;     // groups per pass
+    const int64_t group_stride = (int64_t)nslab * kRowsPerSlab;
+    for (int k0 = 0; k0 < n; k0 += 16) {
+        const int k = k0 + kk < n ? k0 + kk : n - 1;
+        const int64_t col = O[k];
+        uint32_t mx = 0;
+        const int64_t first = ((int64_t)block + (int64_t)(slot / kRowsPerSlab) * nslab) * kRowsPerSlab + slot % kRowsPerSlab;
+        const int64_t step = group_stride * GPP;
+        for (int64_t row = first; row < t; row += 4 * step) {
+            uint32_t v[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                int e = e0 + u * NT;
-                int ec = e < per_group ? e : per_group - 1;
-                int r = ec / n;
-                kk[u] = ec - r * n;
-                int64_t row = r0 + r < t ? r0 + r : t - 1;
-                mag[u] = ((uint32_t)X[row * ldx + O[kk[u]]] & 0x7FFFu) << 16;   // |x| as fp32 bits
+                const int64_t r = row + u * step;
+                v[u] = (uint32_t)X[(r < t ? r : t - 1) * ldx + col] & 0x7FFFu;   // (a repeated row changes no maximum)
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
-                if (e0 + u * NT < per_group) atomicMax(&smax[kk[u]], mag[u]);
+            for (int u = 0; u < 4; ++u) mx = v[u] > mx ? v[u] : mx;
         }
+        // the four row slots of a wavefront, then the wavefronts
+        mx = max(mx, (uint32_t)__shfl_xor((int)mx, 16, 64));
+        mx = max(mx, (uint32_t)__shfl_xor((int)mx, 32, 64));
+        if ((threadIdx.x & 63) < 16) wred[(threadIdx.x >> 6) * 16 + kk] = mx;
+        __syncthreads();
+        if (threadIdx.x < 16 && k0 + kk < n) {
+            uint32_t m = 0;
+#pragma unroll
+            for (int w = 0; w < NWAVE; ++w) m = max(m, wred[w * 16 + kk]);
+            part[(int64_t)block * n + k0 + kk] = m << 16;                              // |x| as fp32 bits
+        }
+        __syncthreads();
     }
-    __syncthreads();
-    for (int k = threadIdx.x; k < n; k += NT) part[(int64_t)block * n + k] = smax[k];
 }
 
 // Eq. 7 with Eq. 8 for one outlier channel, in fp32 with one rounding per operation
