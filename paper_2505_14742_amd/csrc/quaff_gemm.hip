@@ -35,7 +35,7 @@ template <int BM, int BN, int WGM, int WGN, int STAGES, int MINB, int PAIR = 0, 
 static hipError_t launch_dma(const GemmArgs& g, bool dump, hipStream_t stream) {
     using C = DmaCfg<BM, BN, WGM, WGN, STAGES>;
     int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (int)((g.N + BN - 1) / BN);
-    TileMap tm = make_tile_map(tiles_m, tiles_n);
+    TileMap tm = make_tile_map(tiles_m, tiles_n, BM, BN);
     // x = XCD, (z, y) = tile inside its region; a split contraction doubles y (the two halves of a tile are neighbours)
     dim3 grid(8, (unsigned)tm.rn * KSPLIT, (unsigned)tm.rm), block(C::NT);
     if (tm.rn * KSPLIT > 65535 || tm.rm > 65535) return hipErrorInvalidValue;
