@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libquaff.so")
 
-SOURCES = ["quaff_api.cpp", "quaff_prepare.hip", "quaff_scale.hip", "quaff_quant.hip", "quaff_lora.hip", "quaff_quant_lora.hip", "quaff_fwd_step.hip", "quaff_fwd_prep.hip", "quaff_what_quant.hip", "quaff_lora_grad.hip", "quaff_outlier_grad.hip", "quaff_calib.hip",
+SOURCES = ["quaff_api.cpp", "quaff_prepare.hip", "quaff_scale.hip", "quaff_quant.hip", "quaff_lora.hip", "quaff_lora_stream.hip", "quaff_quant_lora.hip", "quaff_fwd_step.hip", "quaff_fwd_prep.hip", "quaff_what_quant.hip", "quaff_lora_grad.hip", "quaff_outlier_grad.hip", "quaff_calib.hip",
            "quaff_gemm.hip", "quaff_profile.cpp", "quaff_microbench.hip"]
 
 # -ffp-contract=off: the quantizer's fp32 operation sequence is part of the arithmetic contract (no fused

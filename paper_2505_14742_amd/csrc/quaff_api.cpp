@@ -598,7 +598,9 @@ int quaff_linear_fwd_step(const uint16_t* X, int64_t t, int64_t c_in, int64_t ld
         return hip_status(quaff::launch_gemm(g, false, s));
     }
     float* wsf = static_cast<float*>(workspace);
-    const int nslab = quaff::scale_update_gather_slabs(t, n_outlier);
+    // (the persistent down-projection of long inputs yields the abs-max slabs itself, one per row group)
+    const int nslab = quaff::lora_stream_applies(lora_rank, t, c_in, n_outlier) ? quaff::lora_stream_row_groups(t)
+                                                                                : quaff::scale_update_gather_slabs(t, n_outlier);
     uint32_t* part = reinterpret_cast<uint32_t*>(wsf);
     float* s_prev = wsf + (int64_t)nslab * n_outlier;
     int st = hip_status(quaff::launch_colmax_lora(X, t, c_in, ldx, O, n_outlier, part, s_O, s_prev, nslab, lora_A,

@@ -28,6 +28,9 @@ hipError_t launch_colmax_lora(const uint16_t* X, int64_t t, int64_t c, int64_t l
                               float scale, uint16_t* T_hi, uint16_t* T_lo, const uint16_t* B, uint16_t* Bt,
                               int64_t c_out, hipStream_t stream, uint16_t* At_scratch) {
     ProfScope prof(K_COLMAX_LORA, stream);
+    if (lora_stream_applies(r, t, c, n) && nslab == lora_stream_row_groups(t))
+        return launch_lora_stream(X, t, c, ldx, A, false, scale, T_hi, T_lo, B, Bt, (int64_t)r, c_out, O, n, part, s_O,
+                                  s_prev, stream);
     const bool transposed = At_scratch && lora_prefers_transposed(r, t);
     if (transposed) {
         hipError_t e = launch_transpose_bf16(A, c, r, At_scratch, stream);

@@ -113,6 +113,16 @@ bool launch_quant_lora(const uint16_t* X, int64_t t, int64_t c, int64_t ldx, con
                        const uint16_t* L_r_by_c, int32_t r, float scale, uint16_t* T_hi, uint16_t* T_lo,
                        hipStream_t stream, hipError_t* err);
 
+// Persistent LoRA down-projection for long inputs at rank 16 (quaff_lora_stream.hip): same bits as launch_lora_down.
+// With O / part / s_O / s_prev (n > 0) the same pass writes the abs-max slabs part [lora_stream_row_groups(t) x n] of the
+// outlier columns and copies s_O to s_prev, as the stand-alone abs-max kernel does.
+bool lora_stream_applies(int32_t r, int64_t t, int64_t c, int32_t n_colmax);
+int lora_stream_row_groups(int64_t t);
+hipError_t launch_lora_stream(const uint16_t* X, int64_t t, int64_t c, int64_t ldx, const uint16_t* L, bool L_is_r_by_c,
+                              float scale, uint16_t* T_hi, uint16_t* T_lo, const uint16_t* tr_src, uint16_t* tr_dst,
+                              int64_t tr_rows, int64_t tr_cols, const int32_t* O, int32_t n, uint32_t* part,
+                              const float* s_O, float* s_prev, hipStream_t stream);
+
 // Pieces of the fused forward step (quaff_linear_fwd_step): the abs-max slabs and the LoRA down-projection of X in
 // one launch (quaff_fwd_step.hip), then the momentum / what kernel on those slabs (quaff_scale.hip).
 int scale_update_gather_slabs(int64_t t, int32_t n);   // slab count the gather variant of the abs-max uses

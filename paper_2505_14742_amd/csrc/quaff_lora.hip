@@ -62,6 +62,9 @@ hipError_t launch_lora_down(const uint16_t* X, int64_t t, int64_t c, int64_t ldx
                             uint16_t* tr_dst, int64_t tr_rows, int64_t tr_cols, hipStream_t stream,
                             uint16_t* Lt_scratch) {
     ProfScope prof(K_LORA, stream);
+    if (lora_stream_applies(r, t, c, 0))
+        return launch_lora_stream(X, t, c, ldx, L, L_is_r_by_c, scale, T_hi, T_lo, tr_src, tr_dst, tr_rows, tr_cols,
+                                  nullptr, 0, nullptr, nullptr, nullptr, stream);
     if (!L_is_r_by_c && Lt_scratch && lora_prefers_transposed(r, t)) {
         // a [c x r] factor of rank 32 or more is transposed once (r x c, contraction-contiguous) instead of slice by
         // slice through LDS inside the product: one small launch more, a several times faster product

@@ -303,6 +303,12 @@ EDGE_CASES = [
     # its own and the main product accumulates onto it in the one-pass epilogue; the second case also has an edge tile
     EdgeCase("o_shape_n200_accumulate", 2048, 256, 3072, list(range(0, 250))[:200], 16),
     EdgeCase("o_shape_ragged_n140_accumulate", 2000, 256, 3056, list(range(10, 150)), 32),
+    # long inputs (at least 256 row blocks of 16) at rank 16: the persistent down-projection with the abs-max inside;
+    # outliers at both ends, on both sides of the boundary between the two contraction parts (576 | 2112) and next to
+    # each other inside one lane's eight columns; ragged rows
+    EdgeCase("long_rows_short_slices", 4099, 1040, 64, [0, 1, 7, 8, 519, 575, 576, 1039], 16),
+    EdgeCase("long_rows_six_steps", 4112, 4208, 64, [0, 63, 64, 2111, 2112, 2113, 3000, 3001, 3002, 3003, 4207], 16,
+             zero_rows=[0, 4111]),
 ]
 
 
