@@ -62,11 +62,10 @@ BwdWs ws_bwd(int64_t t, int64_t c_in, int64_t c_out, int32_t r) {
     return w;
 }
 
-struct GradWs { size_t t1_hi, t1_lo, t2_hi, t2_lo, p1_hi, p1_lo, p2_hi, p2_lo, part_a, part_b, at, total; };
+struct GradWs { size_t t1_hi, t1_lo, t2_hi, t2_lo, part_a, part_b, at, total; };
 GradWs ws_grad(int64_t t, int64_t c_in, int64_t c_out, int32_t r) {
     GradWs w{};
     const size_t tbytes = align_up((size_t)quaff::kLoraParts * t * r * 2);
-    const size_t pbytes = align_up((size_t)((t + 31) / 32 * 32) * r * 2);
     int nslab_a, nslab_b, rows;
     quaff::lora_grad_plan(t, c_in, &nslab_a, &rows);
     quaff::lora_grad_plan(t, c_out, &nslab_b, &rows);
@@ -75,10 +74,6 @@ GradWs ws_grad(int64_t t, int64_t c_in, int64_t c_out, int32_t r) {
     w.t1_lo = off; off += tbytes;
     w.t2_hi = off; off += tbytes;
     w.t2_lo = off; off += tbytes;
-    w.p1_hi = off; off += pbytes;
-    w.p1_lo = off; off += pbytes;
-    w.p2_hi = off; off += pbytes;
-    w.p2_lo = off; off += pbytes;
     w.part_a = off; off += align_up((size_t)nslab_a * r * c_in * 4);
     w.part_b = off; off += align_up((size_t)nslab_b * r * c_out * 4);
     w.at = off; off += quaff::lora_prefers_transposed(r, t) ? align_up((size_t)c_in * r * 2) : 0;   // A^T [r x c_in]
@@ -391,20 +386,16 @@ int quaff_lora_bwd_weights(const uint16_t* X, int64_t ldx, const uint16_t* dY, i
     hipStream_t s = static_cast<hipStream_t>(stream);
     char* base = static_cast<char*>(workspace);
     auto u16 = [&](size_t off) { return reinterpret_cast<uint16_t*>(base + off); };
-    // T1 = scale dY B^T (B is [r x c_out]) and T2 = scale X A (A is [c_in x r]), as the hi/lo parts of the down-projection
-    int st = hip_status(quaff::launch_lora_down(dY, t, c_out, lddy, lora_B, true, lora_rank, lora_scale, u16(w.t1_hi),
-                                                u16(w.t1_lo), nullptr, nullptr, 0, 0, s));
-    if (st != QUAFF_OK) return st;
-    st = hip_status(quaff::launch_lora_down(X, t, c_in, ldx, lora_A, false, lora_rank, lora_scale, u16(w.t2_hi),
-                                            u16(w.t2_lo), nullptr, nullptr, 0, 0, s, u16(w.at)));
-    if (st != QUAFF_OK) return st;
-    st = hip_status(quaff::launch_lora_grad_prep(u16(w.t1_hi), u16(w.t1_lo), u16(w.p1_hi), u16(w.p1_lo), u16(w.t2_hi),
-                                                 u16(w.t2_lo), u16(w.p2_hi), u16(w.p2_lo), t, lora_rank, s));
+    // T1 = scale dY B^T (B is [r x c_out]) and T2 = scale X A (A is [c_in x r]), as the hi/lo parts of the
+    // down-projection
+    int st = hip_status(quaff::launch_lora_down_pair(dY, lddy, c_out, lora_B, u16(w.t1_hi), u16(w.t1_lo), X, ldx, c_in,
+                                                     lora_A, u16(w.t2_hi), u16(w.t2_lo), t, lora_rank, lora_scale,
+                                                     u16(w.at), s));
     if (st != QUAFF_OK) return st;
     // dA^T [r x c_in] = T1^T X, stored transposed;  dB [r x c_out] = T2^T dY
-    return hip_status(quaff::launch_lora_grad_pair(X, ldx, c_in, u16(w.p1_hi), u16(w.p1_lo),
+    return hip_status(quaff::launch_lora_grad_pair(X, ldx, c_in, u16(w.t1_hi), u16(w.t1_lo),
                                                    reinterpret_cast<float*>(base + w.part_a), dA, dY, lddy, c_out,
-                                                   u16(w.p2_hi), u16(w.p2_lo),
+                                                   u16(w.t2_hi), u16(w.t2_lo),
                                                    reinterpret_cast<float*>(base + w.part_b), dB, t, lora_rank, s));
 }
 
@@ -436,13 +427,11 @@ int quaff_linear_bwd_step(const uint16_t* dY, int64_t t, int64_t lddy, const uin
         int st = hip_status(quaff::launch_lora_down(X, t, c_in, ldx, lora_A, false, lora_rank, lora_scale, u16(w.t2_hi),
                                                     u16(w.t2_lo), nullptr, nullptr, 0, 0, gs, u16(w.at)));
         if (st != QUAFF_OK) return st;
-        st = hip_status(quaff::launch_lora_grad_prep(t1_hi, t1_lo, u16(w.p1_hi), u16(w.p1_lo), u16(w.t2_hi),
-                                                     u16(w.t2_lo), u16(w.p2_hi), u16(w.p2_lo), t, lora_rank, gs));
-        if (st != QUAFF_OK) return st;
-        return hip_status(quaff::launch_lora_grad_pair(X, ldx, c_in, u16(w.p1_hi), u16(w.p1_lo),
+        return hip_status(quaff::launch_lora_grad_pair(X, ldx, c_in, t1_hi, t1_lo,
                                                        reinterpret_cast<float*>(base + w.part_a), dA, dY, lddy, c_out,
-                                                       u16(w.p2_hi), u16(w.p2_lo),
-                                                       reinterpret_cast<float*>(base + w.part_b), dB, t, lora_rank, gs));
+                                                       u16(w.t2_hi), u16(w.t2_lo),
+                                                       reinterpret_cast<float*>(base + w.part_b), dB, t, lora_rank,
+                                                       gs));
     };
     // With a second stream and two events from the caller, the weight gradients (short, memory-bound kernels) run
     // beside the input-gradient product (long, MFMA-bound): forked from `stream` once T1 exists, joined back into it

@@ -75,6 +75,13 @@ hipError_t launch_lora_down(const uint16_t* X, int64_t t, int64_t c, int64_t ldx
                             int32_t r, float scale, uint16_t* T_hi, uint16_t* T_lo, const uint16_t* tr_src,
                             uint16_t* tr_dst, int64_t tr_rows, int64_t tr_cols, hipStream_t stream,
                             uint16_t* Lt_scratch = nullptr);
+// The two down-projections of the LoRA weight gradients, T1 = scale dY B^T (B [r x c_out]) and T2 = scale X A
+// (A [c_in x r]), in one launch where that is possible (rank 16, inputs short enough for the per-block kernel), else
+// one after the other; same bits as two launch_lora_down calls.
+hipError_t launch_lora_down_pair(const uint16_t* dY, int64_t lddy, int64_t c_out, const uint16_t* B, uint16_t* T1_hi,
+                                 uint16_t* T1_lo, const uint16_t* X, int64_t ldx, int64_t c_in, const uint16_t* A,
+                                 uint16_t* T2_hi, uint16_t* T2_lo, int64_t t, int32_t r, float scale,
+                                 uint16_t* At_scratch, hipStream_t stream);
 // A [c x r] factor of rank 32 or more is better transposed once to [r x c] (scratch of c * r elements) than slice by
 // slice through LDS by every workgroup (the result is the same bit for bit).  At rank 16 it is not, not even with
 // 1024 row blocks: 16384 x 5120 takes 118 us with the transposed copy against 89 us without (measured).
@@ -82,15 +89,13 @@ inline bool lora_prefers_transposed(int32_t r, int64_t /*t*/) { return r >= 32; 
 hipError_t launch_transpose_bf16(const uint16_t* src, int64_t rows, int64_t cols, uint16_t* dst, hipStream_t stream);
 
 // LoRA weight gradients (quaff_lora_grad.hip).  lora_grad_plan: how the token range is cut into slabs (workspace
-// sizing); prep: fold the hi/lo parts of two down-projections into token-contiguous [r x t_pad] pairs;
-// launch_lora_grad_pair: both gradient products (out = sum_i P[i, :]^T Q[i, :], partial [nslab x r x c] scratch each).
+// sizing); launch_lora_grad_pair: both gradient products (out = sum_i P[i, :]^T Q[i, :]) in one launch, P given as
+// the hi / lo parts [kLoraParts x t x r] of a down-projection, followed by the launch that sums the slabs; partial
+// [nslab x r x c] scratch each.
 void lora_grad_plan(int64_t t, int64_t c, int* nslab, int* rows_per_slab);
-hipError_t launch_lora_grad_prep(const uint16_t* T1_hi, const uint16_t* T1_lo, uint16_t* Pt1_hi, uint16_t* Pt1_lo,
-                                 const uint16_t* T2_hi, const uint16_t* T2_lo, uint16_t* Pt2_hi, uint16_t* Pt2_lo,
-                                 int64_t t, int32_t r, hipStream_t stream);
-hipError_t launch_lora_grad_pair(const uint16_t* X, int64_t ldx, int64_t c_in, const uint16_t* Pt1_hi,
-                                 const uint16_t* Pt1_lo, float* partial_a, float* dA, const uint16_t* dY, int64_t lddy,
-                                 int64_t c_out, const uint16_t* Pt2_hi, const uint16_t* Pt2_lo, float* partial_b,
+hipError_t launch_lora_grad_pair(const uint16_t* X, int64_t ldx, int64_t c_in, const uint16_t* T1_hi,
+                                 const uint16_t* T1_lo, float* partial_a, float* dA, const uint16_t* dY, int64_t lddy,
+                                 int64_t c_out, const uint16_t* T2_hi, const uint16_t* T2_lo, float* partial_b,
                                  float* dB, int64_t t, int32_t r, hipStream_t stream);
 
 // Full-precision dX on the outlier channels (quaff_outlier_grad.hip).  Scratch: L [64 x c_out] bf16,

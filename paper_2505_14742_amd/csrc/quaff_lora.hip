@@ -25,6 +25,22 @@ lora_down_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx, 
                               tr_dst, tr_rows, tr_cols);
 }
 
+// Two rank-16 down-projections of matrices with the same number of rows in one launch: blockIdx.z = 0 multiplies X0 by
+// a contraction-contiguous factor L0 [r x c0], blockIdx.z = 1 multiplies X1 by L1 [c1 x r].
+struct LoraPairArgs {
+    const uint16_t* X[2]; int c[2]; int64_t ldx[2]; const uint16_t* L[2]; uint16_t* T_hi[2]; uint16_t* T_lo[2];
+    int64_t t; float scale; int row_blocks;
+};
+__global__ void __launch_bounds__(64 * kLoraWaves, 8)
+lora_down_pair_kernel(LoraPairArgs a) {
+    if (blockIdx.z == 0)
+        lora_down_body<1, true>(blockIdx.x, blockIdx.y, gridDim.x, a.X[0], a.t, a.c[0], a.ldx[0], a.L[0], a.scale, a.T_hi[0],
+                                a.T_lo[0], a.row_blocks, nullptr, nullptr, 0, 0);
+    else
+        lora_down_body<1, false>(blockIdx.x, blockIdx.y, gridDim.x, a.X[1], a.t, a.c[1], a.ldx[1], a.L[1], a.scale, a.T_hi[1],
+                                 a.T_lo[1], a.row_blocks, nullptr, nullptr, 0, 0);
+}
+
 template <bool L_RC>
 static void dispatch(int R16, dim3 grid, hipStream_t stream, const uint16_t* X, int64_t t, int c, int64_t ldx,
                      const uint16_t* L, float scale, uint16_t* T_hi, uint16_t* T_lo, int row_blocks,
@@ -86,6 +102,25 @@ hipError_t launch_lora_down(const uint16_t* X, int64_t t, int64_t c, int64_t ldx
     else
         dispatch<false>(r / 16, grid, stream, X, t, (int)c, ldx, L, scale, T_hi, T_lo, row_blocks, tr_src, tr_dst,
                         tr_rows, tr_cols);
+    return hipGetLastError();
+}
+
+hipError_t launch_lora_down_pair(const uint16_t* dY, int64_t lddy, int64_t c_out, const uint16_t* B, uint16_t* T1_hi,
+                                 uint16_t* T1_lo, const uint16_t* X, int64_t ldx, int64_t c_in, const uint16_t* A,
+                                 uint16_t* T2_hi, uint16_t* T2_lo, int64_t t, int32_t r, float scale,
+                                 uint16_t* At_scratch, hipStream_t stream) {
+    if (r != 16 || lora_stream_applies(r, t, c_out, 0) || lora_stream_applies(r, t, c_in, 0)) {
+        hipError_t e = launch_lora_down(dY, t, c_out, lddy, B, true, r, scale, T1_hi, T1_lo, nullptr, nullptr, 0, 0,
+                                        stream);
+        if (e != hipSuccess) return e;
+        return launch_lora_down(X, t, c_in, ldx, A, false, r, scale, T2_hi, T2_lo, nullptr, nullptr, 0, 0, stream,
+                                At_scratch);
+    }
+    ProfScope prof(K_LORA, stream);
+    const int row_blocks = (int)((t + 15) / 16);
+    LoraPairArgs a{{dY, X}, {(int)c_out, (int)c_in}, {lddy, ldx}, {B, A}, {T1_hi, T2_hi}, {T1_lo, T2_lo},
+                   t, scale, row_blocks};
+    hipLaunchKernelGGL(lora_down_pair_kernel, dim3(row_blocks, kLoraParts, 2), dim3(64 * kLoraWaves), 0, stream, a);
     return hipGetLastError();
 }
 

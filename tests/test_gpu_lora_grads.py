@@ -35,6 +35,12 @@ def _run(X, dY, A, B, scale, tag):
     dA2, dB2 = torch.empty_like(dA), torch.empty_like(dB)
     q.lora_bwd_weights(Xd, Gd, Ad, Bd, r, scale, dA2, dB2, ws)
     assert torch.equal(dA, dA2) and torch.equal(dB, dB2), tag + " not reproducible"
+    # a third call on the workspace the second one left, with the scale doubled: a power of two scales every
+    # intermediate exactly, so the results must be exactly twice the first ones (partial results or ticket counts
+    # left over from the call before would show here)
+    dA3, dB3 = torch.empty_like(dA), torch.empty_like(dB)
+    q.lora_bwd_weights(Xd, Gd, Ad, Bd, r, 2.0 * scale, dA3, dB3, ws)
+    assert torch.equal(dA3, 2.0 * dA) and torch.equal(dB3, 2.0 * dB), tag + " stale workspace contents used"
     _say("%s ok: dA err %.2e dB err %.2e" % (tag, ea, eb))
 
 
