@@ -587,6 +587,25 @@ def main():
         "stream_copy_GBs_read_plus_write": round(copy_gbs, 1),
         "gemm_frac_of_random_operand_mfma_rate": round(gemm_tops / mf_rand, 4)}
 
+    if not args.no_extras:
+        # Context only, no part of the product: the vendor library's plain int8 product with int32 output (no
+        # dequantisation, no outlier correction, no LoRA add) at the headline GEMM shapes, through torch._int_mm.
+        vendor = {}
+        try:
+            for name, (m_, k_, n_) in (("qkv.fwd", (2048, 3072, 9216)), ("qkv.bwd_dx", (2048, 9216, 3072)),
+                                        ("o_proj", (2048, 3072, 3072))):
+                a8 = torch.randint(-127, 128, (m_, k_), dtype=torch.int8, device=DEV)
+                b8 = torch.randint(-127, 128, (k_, n_), dtype=torch.int8, device=DEV)
+                for _ in range(3):
+                    torch._int_mm(a8, b8)
+                v_ms, _ = time_steps(lambda i: torch._int_mm(a8, b8), 20)
+                vendor[name] = {"us": round(v_ms * 1e3, 2), "tops": round(2.0 * m_ * k_ * n_ / (v_ms * 1e-3) / 1e12, 1)}
+                del a8, b8
+            vendor["what"] = "torch._int_mm (vendor library), int32 output, back-to-back launches timed with events"
+        except Exception as e:      # not available in this build of the vendor stack: recorded, not fatal
+            vendor = {"unavailable": str(e)[:200]}
+        out["measured_ceilings"]["vendor_library_int8_gemm"] = vendor
+
     if not args.no_cpu_baseline:
         # the oracle as it stands on the host cores over the same workload, until about 10 s of CPU work are timed
         from oracle import api as orc
