@@ -16,8 +16,9 @@ colmax_lora_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx
     __shared__ uint32_t wred[16 * kLoraWaves];
     const int lora_blocks = lora_nbx * kLoraParts;
     if ((int)blockIdx.x < lora_blocks)
-        lora_down_body<R16, L_RC>(blockIdx.x % lora_nbx, blockIdx.x / lora_nbx, lora_nbx, X, t, c, ldx, L, scale, T_hi,
-                                   T_lo, row_blocks, tr_src, tr_dst, tr_rows, tr_cols);
+        lora_down_body<R16, L_RC, L_RC ? lora_row_groups(R16) : 1>(blockIdx.x % lora_nbx, blockIdx.x / lora_nbx, lora_nbx, X,
+                                                                    t, c, ldx, L, scale, T_hi, T_lo, row_blocks, tr_src,
+                                                                    tr_dst, tr_rows, tr_cols);
     else
         colmax_outlier_body<64 * kLoraWaves>(blockIdx.x - lora_blocks, nslab, wred, X, t, ldx, O, n, part, s_O, s_prev);
 }
@@ -37,7 +38,8 @@ hipError_t launch_colmax_lora(const uint16_t* X, int64_t t, int64_t c, int64_t l
         if (e != hipSuccess) return e;
         A = At_scratch;
     }
-    const int row_blocks = (int)((t + 15) / 16);
+    const int rows = transposed ? lora_rows_per_block(r) : 16;        // rows per down-projection workgroup
+    const int row_blocks = (int)((t + rows - 1) / rows);
     int64_t b = ((int64_t)r * c_out + 2047) / 2048;
     const int tr_blocks = (int)(b < 128 ? (b > 0 ? b : 1) : 128);
     const int lora_nbx = row_blocks + tr_blocks;

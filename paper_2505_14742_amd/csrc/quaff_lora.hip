@@ -21,8 +21,8 @@ __global__ void __launch_bounds__(64 * kLoraWaves, R16 <= 2 ? 8 : 4)
 lora_down_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx, const uint16_t* __restrict__ L,
                  float scale, uint16_t* __restrict__ T_hi, uint16_t* __restrict__ T_lo, int row_blocks,
                  const uint16_t* __restrict__ tr_src, uint16_t* __restrict__ tr_dst, int64_t tr_rows, int64_t tr_cols) {
-    lora_down_body<R16, L_RC>(blockIdx.x, blockIdx.y, gridDim.x, X, t, c, ldx, L, scale, T_hi, T_lo, row_blocks, tr_src,
-                              tr_dst, tr_rows, tr_cols);
+    lora_down_body<R16, L_RC, L_RC ? lora_row_groups(R16) : 1>(blockIdx.x, blockIdx.y, gridDim.x, X, t, c, ldx, L, scale,
+                                                                T_hi, T_lo, row_blocks, tr_src, tr_dst, tr_rows, tr_cols);
 }
 
 // Two rank-16 down-projections of matrices with the same number of rows in one launch: blockIdx.z = 0 multiplies X0 by
@@ -89,7 +89,8 @@ hipError_t launch_lora_down(const uint16_t* X, int64_t t, int64_t c, int64_t ldx
         L = Lt_scratch;
         L_is_r_by_c = true;
     }
-    int row_blocks = (int)((t + 15) / 16);
+    const int rows = L_is_r_by_c ? lora_rows_per_block(r) : 16;      // rows per workgroup
+    int row_blocks = (int)((t + rows - 1) / rows);
     int tr_blocks = 0;
     if (tr_src) {
         int64_t b = (tr_rows * tr_cols + 2047) / 2048;

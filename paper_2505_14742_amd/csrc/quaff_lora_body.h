@@ -12,25 +12,35 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kLoraWaves = 16;
 // contraction steps whose loads are issued together (latency hiding); even.  With the contraction-contiguous factor
 // and r = 16 a wavefront's whole slice of a 9216-wide row (ten steps) is in flight at once.
-template <int R16, bool L_RC> struct LoraUnroll { static constexpr int value = (L_RC && R16 == 1) ? 10 : 6; };
+template <int R16, bool L_RC, int RG = 1> struct LoraUnroll {
+    static constexpr int value = RG == 2 ? 2 : (L_RC && R16 == 1) ? 10 : 6;
+};
+// Row groups of 16 rows per workgroup.  From rank 48 on a workgroup takes 32 rows: every workgroup fetches its share of
+// L (c x r against 16 x c of rows: four times the rows' bytes at rank 64), and its 128 registers per lane leave room
+// for one 16-wavefront workgroup per compute unit only, so 16-row workgroups would also need two rounds at 4096 rows.
+// Measured at rank 64, 4096 rows: abs-max + down-projection launch 43 -> 30 us at 4096 columns, 86 -> 64 us at 11008;
+// backward quantizer + down-projection launch 44 -> 30 us and 96 -> 80 us.
+constexpr int lora_row_groups(int R16) { return R16 >= 3 ? 2 : 1; }
+inline int lora_rows_per_block(int r) { return 16 * lora_row_groups(r / 16); }
 
 __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
     uint32_t u = __float_as_uint(f);
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
-// R16 = r / 16 column blocks of T.  L_RC: L is [r x c] (contraction-contiguous) else [c x r].
-// Work of one workgroup (64 * kLoraWaves threads): `bx` < row_blocks is its 16-row block and `by` its part of the
+// R16 = r / 16 column blocks of T.  L_RC: L is [r x c] (contraction-contiguous) else [c x r].  RG = row groups of 16 rows.
+// Work of one workgroup (64 * kLoraWaves threads): `bx` < row_blocks is its block of 16 RG rows and `by` its part of the
 // contraction range; workgroups bx >= row_blocks (nbx in all, by = 0 only) write the transposed copy.
-template <int R16, bool L_RC>
+template <int R16, bool L_RC, int RG = 1>
 __device__ __forceinline__ void lora_down_body(int bx, int by, int nbx, const uint16_t* __restrict__ X, int64_t t, int c,
                                                int64_t ldx, const uint16_t* __restrict__ L, float scale,
                                                uint16_t* __restrict__ T_hi, uint16_t* __restrict__ T_lo, int row_blocks,
                                                const uint16_t* __restrict__ tr_src, uint16_t* __restrict__ tr_dst,
                                                int64_t tr_rows, int64_t tr_cols) {
+    static_assert(RG == 1 || L_RC, "several row groups only with a contraction-contiguous factor");
     constexpr int r = R16 * 16;
     constexpr int NT = 64 * kLoraWaves;
-    constexpr int kLoraUnroll = LoraUnroll<R16, L_RC>::value;
+    constexpr int kLoraUnroll = LoraUnroll<R16, L_RC, RG>::value;
     constexpr int TROW = 40;                       // padded row (in bf16) of the transposed slice: 32 + 8
     if (bx >= row_blocks) {
         if (by != 0) return;
@@ -47,13 +57,20 @@ __device__ __forceinline__ void lora_down_body(int bx, int by, int nbx, const ui
     __shared__ __attribute__((aligned(16))) uint16_t lt[L_RC ? 1 : kLoraWaves][L_RC ? 1 : r][L_RC ? 8 : TROW];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 15, g = lane >> 4;
-    const int64_t row = (int64_t)bx * 16 + m;
-    const bool live = row < t;
-    const uint16_t* xrow = X + (live ? row : 0) * ldx;
-
-    f32x4 acc[R16];
+    bool live[RG];
+    const uint16_t* xrow[RG];
 #pragma unroll
-    for (int b = 0; b < R16; ++b) acc[b] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int rg = 0; rg < RG; ++rg) {
+        const int64_t row = ((int64_t)bx * RG + rg) * 16 + m;
+        live[rg] = row < t;
+        xrow[rg] = X + (live[rg] ? row : 0) * ldx;
+    }
+
+    f32x4 acc[RG][R16];
+#pragma unroll
+    for (int rg = 0; rg < RG; ++rg)
+#pragma unroll
+        for (int b = 0; b < R16; ++b) acc[rg][b] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
     // each wavefront owns one contiguous slice of the contraction range (kw columns), walked in 32-column steps
     // this workgroup's part of the contraction range, then this wavefront's slice of it
@@ -65,7 +82,7 @@ __device__ __forceinline__ void lora_down_body(int bx, int by, int nbx, const ui
     T_hi += (int64_t)by * t * r;
     T_lo += (int64_t)by * t * r;
     for (int kk0 = kbeg; kk0 < kend; kk0 += 32 * kLoraUnroll) {
-        u32x4 xa[kLoraUnroll], lb[kLoraUnroll][R16];
+        u32x4 xa[kLoraUnroll][RG], lb[kLoraUnroll][R16];
         // all global loads of the batch first
 #pragma unroll
         for (int u = 0; u < kLoraUnroll; ++u) {
@@ -78,8 +95,11 @@ __device__ __forceinline__ void lora_down_body(int bx, int by, int nbx, const ui
             // loads are unconditional (address clamped into the row) so that the whole batch is in flight together;
             // a step past the end contributes zero because its x fragment is cleared
             const int kc = k < kend ? k : c - 8;
-            xa[u] = *reinterpret_cast<const u32x4*>(xrow + kc);
-            if (!(live && k < kend)) xa[u] = (u32x4){0, 0, 0, 0};
+#pragma unroll
+            for (int rg = 0; rg < RG; ++rg) {
+                xa[u][rg] = *reinterpret_cast<const u32x4*>(xrow[rg] + kc);
+                if (!(live[rg] && k < kend)) xa[u][rg] = (u32x4){0, 0, 0, 0};
+            }
             if (L_RC) {
 #pragma unroll
                 for (int b = 0; b < R16; ++b)
@@ -117,29 +137,36 @@ __device__ __forceinline__ void lora_down_body(int bx, int by, int nbx, const ui
                     lb[u][b] = *reinterpret_cast<const u32x4*>(&lt[wave][b * 16 + m][g * 8]);
             }
 #pragma unroll
-            for (int b = 0; b < R16; ++b)
-                acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xa[u]),
-                                                                 __builtin_bit_cast(bf16x8, lb[u][b]), acc[b], 0, 0, 0);
+            for (int rg = 0; rg < RG; ++rg)
+#pragma unroll
+                for (int b = 0; b < R16; ++b)
+                    acc[rg][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xa[u][rg]),
+                                                                         __builtin_bit_cast(bf16x8, lb[u][b]), acc[rg][b],
+                                                                         0, 0, 0);
         }
     }
 #pragma unroll
-    for (int b = 0; b < R16; ++b)
+    for (int rg = 0; rg < RG; ++rg) {
+        if (rg > 0) __syncthreads();               // the sums over the previous row group have been read
 #pragma unroll
-        for (int v = 0; v < 4; ++v) red[wave][b][lane][v] = acc[b][v];
-    __syncthreads();
-    // fixed-order sum over the wavefronts; element v of lane (m, g) is T[row0 + 4 g + v][16 b + m]
-    for (int e = threadIdx.x; e < R16 * 64 * 4; e += NT) {
-        int v = e & 3, ln = (e >> 2) & 63, b = e >> 8;
-        float s = 0.0f;
+        for (int b = 0; b < R16; ++b)
 #pragma unroll
-        for (int w = 0; w < kLoraWaves; ++w) s += red[w][b][ln][v];
-        s = s * scale;
-        int64_t orow = (int64_t)bx * 16 + (ln >> 4) * 4 + v;
-        if (orow < t) {
-            uint32_t hi = f32_to_bf16_rne(s);
-            float rest = s - __uint_as_float(hi << 16);
-            T_hi[orow * r + b * 16 + (ln & 15)] = (uint16_t)hi;
-            T_lo[orow * r + b * 16 + (ln & 15)] = (uint16_t)f32_to_bf16_rne(rest);
+            for (int v = 0; v < 4; ++v) red[wave][b][lane][v] = acc[rg][b][v];
+        __syncthreads();
+        // fixed-order sum over the wavefronts; element v of lane (m, g) is T[row0 + 4 g + v][16 b + m]
+        for (int e = threadIdx.x; e < R16 * 64 * 4; e += NT) {
+            int v = e & 3, ln = (e >> 2) & 63, b = e >> 8;
+            float s = 0.0f;
+#pragma unroll
+            for (int w = 0; w < kLoraWaves; ++w) s += red[w][b][ln][v];
+            s = s * scale;
+            int64_t orow = ((int64_t)bx * RG + rg) * 16 + (ln >> 4) * 4 + v;
+            if (orow < t) {
+                uint32_t hi = f32_to_bf16_rne(s);
+                float rest = s - __uint_as_float(hi << 16);
+                T_hi[orow * r + b * 16 + (ln & 15)] = (uint16_t)hi;
+                T_lo[orow * r + b * 16 + (ln & 15)] = (uint16_t)f32_to_bf16_rne(rest);
+            }
         }
     }
 }

@@ -3,8 +3,8 @@
 // microseconds of ramp-up and drain.  Two forms:
 //   quant_lora_kernel        the first workgroups of the grid take the down-projection (they are the longer ones),
 //                            the rest quantize rows; the two roles share nothing but the launch;
-//   quant_lora_rows8_kernel  (rank 16, rows of up to 5120 columns, at most 4096 rows) one pass over dY: the registers
-//                            that hold a row block as MFMA operands are also what the quantizer works on.
+//   quant_lora_rows8_kernel  (rank 16, rows of up to 5120 columns) one pass over dY: the registers that hold a row
+//                            block as MFMA operands are also what the quantizer works on; persistent workgroups.
 #include "quaff_lora_body.h"
 #include "quaff_quant_body.h"
 
@@ -14,33 +14,26 @@ template <int R16, int TPR, int NV>
 __global__ void __launch_bounds__(64 * kLoraWaves)
 quant_lora_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx, const float* __restrict__ cs,
                   int8_t* __restrict__ Xq, float* __restrict__ delta, const uint16_t* __restrict__ L, float scale,
-                  uint16_t* __restrict__ T_hi, uint16_t* __restrict__ T_lo, int row_blocks) {
-    const int lora_blocks = row_blocks * kLoraParts;
+                  uint16_t* __restrict__ T_hi, uint16_t* __restrict__ T_lo, int lora_row_blocks) {
+    constexpr int RG = lora_row_groups(R16);                 // 16-row groups per down-projection workgroup
+    const int lora_blocks = lora_row_blocks * kLoraParts;
     if ((int)blockIdx.x < lora_blocks)
-        lora_down_body<R16, true>(blockIdx.x % row_blocks, blockIdx.x / row_blocks, row_blocks, X, t, c, ldx, L, scale,
-                                  T_hi, T_lo, row_blocks, nullptr, nullptr, 0, 0);
+        lora_down_body<R16, true, RG>(blockIdx.x % lora_row_blocks, blockIdx.x / lora_row_blocks, lora_row_blocks, X, t, c,
+                                      ldx, L, scale, T_hi, T_lo, lora_row_blocks, nullptr, nullptr, 0, 0);
     else {
         // The hardware deals consecutive workgroups to the eight XCDs in turn and every XCD has its own L2: the
-        // quantizing workgroups of a 16-row block are renumbered so that they land on the XCD whose down-projection
-        // workgroups (index = row block, same residue modulo 8) read the same rows at about the same time.
+        // quantizing workgroups of a row block are renumbered so that they land on the XCD whose down-projection
+        // workgroups (index = row block of 16 RG rows, same residue modulo 8) read the same rows at about the same time.
         constexpr int QPG = 16 / ((64 * kLoraWaves) / TPR);   // quantizing workgroups per 16-row block (1 or 4)
         const int local = blockIdx.x - lora_blocks;
         const int xcd = local & 7, m = local >> 3;
-        const int rb = (m / QPG) * 8 + xcd;                   // row block
+        const int mq = m / QPG;
+        const int rb = ((mq / RG) * 8 + xcd) * RG + mq % RG;   // 16-row block
         quant_rows_body<64 * kLoraWaves, TPR, NV>(rb * QPG + m % QPG, X, t, c, ldx, cs, nullptr, 0, 0, Xq, delta,
                                                   nullptr);
     }
 }
 
-// One pass over dY for both results.  A workgroup of 16 wavefronts owns 8 rows; wavefront w holds its slice of the
-// contraction range in registers, 64 columns per step: lane (m, g) keeps row m % 8, columns 32 (m / 8) + 8 g .. + 7 of
-// the step, so every lane holds data and a row's 64 columns are one 128-byte line.  As the A operand of the 16-row
-// MFMA this is rows 0..7 over the first 32 columns of the step stacked on the same rows over the second 32; two MFMAs
-// per step, one with each half of L as the B operand, leave the first half's products in result rows 0..7 of the one
-// and the second half's in rows 8..15 of the other (the remaining result rows are products of mismatched halves and are
-// dropped).  The same registers then feed the quantizer, once the row maxima have been exchanged through LDS.
-// Wavefronts 0-7 and 8-15 produce the two parts of T.  NSTEP = steps per wavefront; the host picks the smallest
-// instantiation with 8 * 64 * NSTEP >= cp.
 // One pass over dY for both results.  A workgroup of 16 wavefronts owns 8 rows at a time; wavefront w holds its slice
 // of the contraction range in registers, 64 columns per step: lane (m, g) keeps row m % 8, columns 32 (m / 8) + 8 g .. + 7
 // of the step, so every lane holds data and a row's 64 columns are one 128-byte line.  As the A operand of the 16-row
@@ -241,13 +234,16 @@ template <int R16>
 static bool launch_r(const uint16_t* X, int64_t t, int c, int64_t ldx, const float* cs, int8_t* Xq, float* delta,
                      const uint16_t* L, float scale, uint16_t* T_hi, uint16_t* T_lo, hipStream_t stream) {
     constexpr int NT = 64 * kLoraWaves;
+    constexpr int RG = lora_row_groups(R16);
     const int row_blocks = (int)((t + 15) / 16);
+    const int lora_row_blocks = (int)((t + 16 * RG - 1) / (16 * RG));
     const int vec = (c + 7) / 8;
 #define QUAFF_QL(TPR, NV)                                                                                             \
     hipLaunchKernelGGL((quant_lora_kernel<R16, TPR, NV>),                                                             \
-                       dim3((unsigned)(row_blocks * kLoraParts + 8 * ((row_blocks + 7) / 8) * (16 / (NT / TPR)))),   \
+                       dim3((unsigned)(lora_row_blocks * kLoraParts +                                                 \
+                                       8 * RG * ((row_blocks + 8 * RG - 1) / (8 * RG)) * (16 / (NT / TPR)))),         \
                        dim3(NT), 0,                                                                                   \
-                       stream, X, t, c, ldx, cs, Xq, delta, L, scale, T_hi, T_lo, row_blocks)
+                       stream, X, t, c, ldx, cs, Xq, delta, L, scale, T_hi, T_lo, lora_row_blocks)
     if (vec <= 64 * 2) QUAFF_QL(64, 2);
     else if (vec <= 64 * 4) QUAFF_QL(64, 4);
     else if (vec <= 64 * 6) QUAFF_QL(64, 6);
