@@ -35,10 +35,15 @@ template <int BM, int BN, int WGM, int WGN, int STAGES, int MINB, int PAIR = 0, 
 static hipError_t launch_dma(const GemmArgs& g, bool dump, hipStream_t stream) {
     using C = DmaCfg<BM, BN, WGM, WGN, STAGES>;
     int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (int)((g.N + BN - 1) / BN);
-    TileMap tm = make_tile_map(tiles_m, tiles_n, BM, BN);
-    // x = XCD, (z, y) = tile inside its region; a split contraction doubles y (the two halves of a tile are neighbours)
-    dim3 grid(8, (unsigned)tm.rn * KSPLIT, (unsigned)tm.rm), block(C::NT);
-    if (tm.rn * KSPLIT > 65535 || tm.rm > 65535) return hipErrorInvalidValue;
+    TileMap tm = make_tile_map(tiles_m, tiles_n, BM, BN, MINB);
+#ifdef QUAFF_FORCE_GM
+    tm.gm = QUAFF_FORCE_GM < tm.rm ? QUAFF_FORCE_GM : 1;
+#endif
+    // x % 8 = XCD, x / 8 = tile row inside a group of gm, y = tile column, z = group; a split contraction doubles y
+    // (the two halves of a tile are neighbours)
+    const int groups = (tm.rm + tm.gm - 1) / tm.gm;
+    dim3 grid(8 * (unsigned)tm.gm, (unsigned)tm.rn * KSPLIT, (unsigned)groups), block(C::NT);
+    if (tm.rn * KSPLIT > 65535 || groups > 65535) return hipErrorInvalidValue;
     if constexpr (KSPLIT == 2) {
         if (dump || g.C16 || g.accumulate || (int64_t)(g.K2 / 64) * C::K2_PLANES_BYTES > C::EPI_LIMIT)
             return hipErrorInvalidValue;

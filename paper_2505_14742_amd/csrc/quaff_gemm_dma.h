@@ -130,18 +130,24 @@ struct DmaCfg {
 
 // Tile order.  Workgroups are dealt to the eight XCDs round-robin by the hardware and every XCD has its own L2, so
 // the tile grid is cut into XM x XN = 8 rectangular regions, one per XCD: the operand panels an XCD touches are
-// then as few as possible.  The launch grid is (8, rn, rm): workgroups are numbered x fastest, so blockIdx.x is the
-// XCD and (blockIdx.z, blockIdx.y) the tile inside its region - no integer division in the kernel.  Returns false
-// for surplus workgroups of a region that is smaller than the largest one.
+// then as few as possible.  The launch grid is (8 GM, rn, ceil(rm / GM)): workgroups are numbered x fastest, so
+// blockIdx.x % 8 is the XCD, and an XCD receives its tiles in the order: GM consecutive tile rows of tile column 0,
+// the same rows of column 1, ... - no integer division in the kernel.  The 32 (or 64) tiles an XCD works on at the same
+// time are then a block of GM rows by a few columns instead of a strip of one row: with more tiles than compute
+// units the operand panels of the concurrent tiles are what the 4 MB L2 has to hold while the contraction advances
+// (a 16384 x 13824 x 5120 product fetched 4.6 GB past its L2s with GM = 1: every tile row swept all 35 MB of its
+// XCD's B region).  Returns false for surplus workgroups (a region smaller than the largest one, rows past rm).
 struct TileMap {
     int tiles_m, tiles_n, xm, xn, rm, rn;   // region grid xm x xn (powers of two), region size rm x rn (ceil)
     int xn_log2;
+    int gm;                                 // tile rows per group (power of two)
 };
-__device__ __forceinline__ bool tile_of_block(const TileMap& t, int xcd, int ln, int lm, int& tm, int& tn) {
+__device__ __forceinline__ bool tile_of_block(const TileMap& t, int bx, int by, int bz, int& tm, int& tn) {
+    const int xcd = bx & 7, lm = bz * t.gm + (bx >> 3), ln = by;
     const int rx = xcd >> t.xn_log2, ry = xcd & (t.xn - 1);
     tm = rx * t.rm + lm;
     tn = ry * t.rn + ln;
-    return tm < t.tiles_m && tn < t.tiles_n;
+    return lm < t.rm && tm < t.tiles_m && tn < t.tiles_n;
 }
 
 // The main loop.  `dma` and `rd` both point at the LDS ring; they are separate restrict-qualified parameters so that
@@ -1031,8 +1037,8 @@ gemm_i8_dma_kernel(const GemmArgs g, const TileMap tmap) {
 // compute unit for a whole pass), then the operand rows an XCD has to fetch into its own L2: rm * bm rows of A plus
 // rn * bn rows of B, every one K bytes long.  (Eight L2s that share nothing cannot fetch less than the sum of these
 // over the XCDs: 78.6 MB for a 2048 x 9216 x 3072 product in 256 x 288 tiles, against 34.6 MB of operands.)
-inline TileMap make_tile_map(int tiles_m, int tiles_n, int bm, int bn) {
-    TileMap best{tiles_m, tiles_n, 1, 8, tiles_m, (tiles_n + 7) / 8, 3};
+inline TileMap make_tile_map(int tiles_m, int tiles_n, int bm, int bn, int wgs_per_cu) {
+    TileMap best{tiles_m, tiles_n, 1, 8, tiles_m, (tiles_n + 7) / 8, 3, 1};
     long best_cost = -1;
     const int xms[4] = {1, 2, 4, 8};
     for (int xm : xms) {
@@ -1040,7 +1046,17 @@ inline TileMap make_tile_map(int tiles_m, int tiles_n, int bm, int bn) {
         int rm = (tiles_m + xm - 1) / xm, rn = (tiles_n + xn - 1) / xn;
         long cost = (long)rm * rn * 1000000 + (long)rm * bm + (long)rn * bn;
         const int xn_log2 = xn == 1 ? 0 : xn == 2 ? 1 : xn == 4 ? 2 : 3;
-        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = TileMap{tiles_m, tiles_n, xm, xn, rm, rn, xn_log2}; }
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = TileMap{tiles_m, tiles_n, xm, xn, rm, rn, xn_log2, 1}; }
+    }
+    // tile rows per group: the block of concurrent tiles (32 compute units per XCD) with the fewest operand rows
+    const int conc = 32 * wgs_per_cu;
+    if (best.rm * best.rn > conc) {
+        long gcost = -1;
+        for (int gm = 1; gm <= 16 && gm <= best.rm; gm *= 2) {
+            const int cols = (conc + gm - 1) / gm < best.rn ? (conc + gm - 1) / gm : best.rn;
+            const long cst = (long)gm * bm + (long)cols * bn;
+            if (gcost < 0 || cst < gcost) { gcost = cst; best.gm = gm; }
+        }
     }
     return best;
 }
