@@ -1053,8 +1053,10 @@ inline TileMap make_tile_map(int tiles_m, int tiles_n, int bm, int bn, int wgs_p
     if (best.rm * best.rn > conc) {
         long gcost = -1;
         for (int gm = 1; gm <= 16 && gm <= best.rm; gm *= 2) {
+            // concurrent tiles: `cols` columns of as many whole groups as it takes
             const int cols = (conc + gm - 1) / gm < best.rn ? (conc + gm - 1) / gm : best.rn;
-            const long cst = (long)gm * bm + (long)cols * bn;
+            const int groups = (conc + gm * cols - 1) / (gm * cols);
+            const long cst = (long)gm * groups * bm + (long)cols * bn;
             if (gcost < 0 || cst < gcost) { gcost = cst; best.gm = gm; }
         }
     }
