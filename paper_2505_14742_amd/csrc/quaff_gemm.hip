@@ -160,12 +160,22 @@ hipError_t launch_gemm_one(const GemmArgs& g, bool dump_acc, hipStream_t stream)
         if (g.b_layout == kPackedKN) return launch_dma<256, 192, 4, 2, 4, 1, 2, true, 2>(g, false, stream);
         return launch_dma<256, 192, 4, 2, 4, 1, 2, false, 2>(g, false, stream);
     }
+    // The 128 x 192 tile with at most one tile per compute unit takes a ring of three wide stages (120 KB of LDS: one
+    // workgroup per unit): the operands of the stage after next are then in flight too, which is what a product whose
+    // operands come from HBM rather than from the Infinity Cache needs (measured back to back on operand sets that
+    // rotate through more than the cache holds: o_proj forward 36.2 -> 30.5 us, qkv dX 79.2 -> 69.8, 8192 -> 3072
+    // forward 74.1 -> 61.7; on cached operands the two rings are level, 29.4 / 65.6 / 60.1 us).  It is compiled for
+    // the register budget of two workgroups per unit like the two-stage form (with the whole file to itself the
+    // compiler's schedule is 2 - 8 % slower).  With more tiles than units two workgroups per unit overlap each
+    // other's epilogues instead, which needs the smaller ring.
+    const bool one_round = ((g.M + 127) / 128) * ((g.N + 191) / 192) <= 256;
     if (g.b_layout == kPackedKN) {
         switch (choose_tile(g.M, g.N)) {
             case 0: return launch_dma<256, 256, 2, 4, 4, 1, 2, true>(g, dump_acc, stream);
             case 1: return launch_dma<256, 288, 4, 3, 4, 1, 2, true>(g, dump_acc, stream);
             case 2: return launch_dma<256, 128, 4, 2, 4, 1, 2, true>(g, dump_acc, stream);
-            default: return launch_dma<128, 192, 2, 2, 4, 2, 2, true>(g, dump_acc, stream);
+            default: return one_round ? launch_dma<128, 192, 2, 2, 6, 2, 2, true>(g, dump_acc, stream)
+                                      : launch_dma<128, 192, 2, 2, 4, 2, 2, true>(g, dump_acc, stream);
         }
     }
     // contractions that are a multiple of 128 run the wide-stage main loop (128-byte row segments per direct load)
@@ -177,7 +187,8 @@ hipError_t launch_gemm_one(const GemmArgs& g, bool dump_acc, hipStream_t stream)
                             : launch_dma<256, 288, 4, 3, 3, 1>(g, dump_acc, stream);
         case 2: return wide ? launch_dma<256, 128, 4, 2, 4, 1, 2>(g, dump_acc, stream)
                             : launch_dma<256, 128, 4, 2, 3, 1>(g, dump_acc, stream);
-        default: return wide ? launch_dma<128, 192, 2, 2, 4, 2, 2>(g, dump_acc, stream)
+        default: return wide ? (one_round ? launch_dma<128, 192, 2, 2, 6, 2, 2>(g, dump_acc, stream)
+                                          : launch_dma<128, 192, 2, 2, 4, 2, 2>(g, dump_acc, stream))
                              : launch_dma<128, 192, 2, 2, 4, 2>(g, dump_acc, stream);
     }
 }
