@@ -248,6 +248,49 @@ def kernel_stats(layers, kinds, launches, nsteps, copy_gbs):
     return kernels
 
 
+def gemm_cold_vs_warm(layers):
+    """GEMM launch times of each projection with its operands cached (one operand set used again and again) and from
+    HBM (enough copies of the operand set used in turn, more than 640 MB in all, that none is left in the 256 MB
+    Infinity Cache when its turn comes), back to back without idling.  The codes of the weight are copied device to
+    device; activations and gradients are random codes."""
+    import torch
+    from paper_2505_14742_amd import binding as q
+    res = {}
+    for L in layers:
+        p, n, r = L["p"], L["n"], L["r"]
+        t, K, N = p.t, p.c_in, p.c_out
+        nset = max(2, int(640e6 / (t * K + K * N + 4 * t * N + 2 * t * N + 4 * t * K)) + 1)
+        sets = [dict(Xq=torch.randint(-40, 41, (t, K), dtype=torch.int8, device=DEV), Wq=L["Wq"].clone(),
+                     dY=L["dY"][0].clone(), Y=torch.empty_like(L["Y"][0]), dX=torch.empty_like(L["dX"][0]))
+                for _ in range(nset)]
+        row = {}
+        for mode in ("cached", "from_hbm"):
+            for which in ("fwd", "bwd_dx"):
+                def call(i):
+                    S = sets[i % nset] if mode == "from_hbm" else sets[0]
+                    if which == "fwd":
+                        q.linear_fwd(S["Xq"], L["dx"], L["xo"] if n else None, S["Wq"], L["dw"], K, N,
+                                     L["what"] if n else None, L["dwh"] if n else None, n, L["X"][0] if r else None,
+                                     L["A"], L["B"], r, p.lora_scale, S["Y"], L["ws"])
+                    else:
+                        q.linear_bwd_dx(S["dY"], S["Wq"], L["dw"], K, N, L["A"], L["B"], r, p.lora_scale, S["dX"], L["ws"])
+                for i in range(nset + 2):
+                    call(i)
+                torch.cuda.synchronize()
+                q.profile_enable(True)
+                for i in range(2 * nset + 4):
+                    call(i)
+                torch.cuda.synchronize()
+                ts = sorted(x[1] * 1e3 for x in q.profile_launches() if x[0] == "gemm_i8")
+                q.profile_enable(False)
+                row["%s.%s_us" % (which, mode)] = round(ts[len(ts) // 2], 2)
+        row["operand_sets"] = nset
+        res[p.name] = row
+        del sets
+        torch.cuda.empty_cache()
+    return res
+
+
 def workload_name(cfg, layers):
     shapes = ", ".join("%s t=%d %d->%d |O|=%d r=%d" % (L["p"].name, L["p"].t, L["p"].c_in, L["p"].c_out, L["n"], L["r"])
                        for L in layers)
@@ -576,6 +619,7 @@ def main():
                 ns, rows, p0.c_in, Oc.numel()),
             "algorithmic_GBs": round(2.0 * ns * rows * p0.c_in / (c_ms * 1e-3) / 1e9, 1),
             "channels_selected": int(nc.item())}
+        extra["gemm_operands_cached_vs_from_hbm"] = gemm_cold_vs_warm(layers)
         out["beyond_headline"] = extra
 
     # measured ceilings next to the published peaks (register-only MFMA loop, streaming copy)
