@@ -255,13 +255,15 @@ hipError_t launch_lora_stream(const uint16_t* X, int64_t t, int64_t c, int64_t l
                      O, n, part, s_O, s_prev};
     const dim3 grid((unsigned)lora_stream_row_groups(t), kLoraParts), block(64 * kLoraWaves);
     const bool colmax = n > 0 && O && part;
+    if (colmax && L_is_r_by_c) return hipErrorInvalidValue;   // the abs-max rides on the forward factor A [c x r] only
     const int ns = stream_steps(c);
 #define QUAFF_LS4(NS, HB, PF, RC, CM)                                                                        \
     hipLaunchKernelGGL((lora_stream_kernel<NS, HB, PF, RC, CM>), grid, block, 0, stream, a)
 #define QUAFF_LS(NS, HB, PF)                                                                                 \
     {                                                                                                        \
-        if (L_is_r_by_c) { if (colmax) QUAFF_LS4(NS, HB, PF, true, true); else QUAFF_LS4(NS, HB, PF, true, false); }   \
-        else { if (colmax) QUAFF_LS4(NS, HB, PF, false, true); else QUAFF_LS4(NS, HB, PF, false, false); }   \
+        if (L_is_r_by_c) QUAFF_LS4(NS, HB, PF, true, false);                                                 \
+        else if (colmax) QUAFF_LS4(NS, HB, PF, false, true);                                                 \
+        else QUAFF_LS4(NS, HB, PF, false, false);                                                            \
     }
     if (ns <= 4) QUAFF_LS(4, 4, true)
     else if (ns <= 6) QUAFF_LS(6, 6, true)
