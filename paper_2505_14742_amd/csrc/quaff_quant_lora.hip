@@ -52,7 +52,9 @@ __device__ __forceinline__ void lds_barrier() {
     asm volatile("" ::: "memory");
 }
 
-template <int R16, int NSTEP>
+// RESIDENT = false: rows too long to keep a slice of L and a second group of rows in registers; L is fetched (from L2,
+// where it stays) a few steps at a time for every group and the next group's rows are not requested ahead.
+template <int R16, int NSTEP, bool RESIDENT = true>
 __global__ void __launch_bounds__(64 * kLoraWaves)
 quant_lora_rows8_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_t ldx, const float* __restrict__ cs,
                         int8_t* __restrict__ Xq, float* __restrict__ delta, const uint16_t* __restrict__ L, float scale,
@@ -67,7 +69,8 @@ quant_lora_rows8_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_
     extern __shared__ __attribute__((aligned(16))) float cs_copy[];   // [c], then the wavefronts' code rows
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 15, g = lane >> 4;
-    char* cw = reinterpret_cast<char*>(cs_copy) + (((size_t)c * 4 + 255) & ~(size_t)255) + wave * (8 * NSTEP * 64);
+    constexpr int PS = NSTEP > 9 ? (NSTEP + 1) / 2 : NSTEP;      // steps whose codes are staged together
+    char* cw = reinterpret_cast<char*>(cs_copy) + (((size_t)c * 4 + 255) & ~(size_t)255) + wave * (8 * PS * 64);
 
     const int part = wave >> 3;
     const int cp = ((c + kLoraParts * 64 - 1) / (kLoraParts * 64)) * 64;
@@ -89,20 +92,28 @@ quant_lora_rows8_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_
             if (live && k < kend) dst[u] = *reinterpret_cast<const u32x4*>(xrow + k);
         }
     };
-    u32x4 xa[NSTEP], xn[NSTEP];
+    u32x4 xa[NSTEP], xn[NSTEP];                    // (xn costs no registers when RESIDENT is false)
     load_rows(blockIdx.x, xa);
-    u32x4 lb[NSTEP][2][R16];
+    constexpr int BU = NSTEP > 9 ? 2 : 3;          // RESIDENT = false: steps whose fragments of L are in flight together
+    constexpr int LSTEPS = RESIDENT ? NSTEP : BU;
+    u32x4 lb[LSTEPS][2][R16];
+    auto load_l = [&](int u0) {
 #pragma unroll
-    for (int u = 0; u < NSTEP; ++u)
+        for (int uu = 0; uu < LSTEPS; ++uu)
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int k = lcol_of(u, h), kc = k < kend ? k : c - 8;
+            for (int h = 0; h < 2; ++h) {
+                const int k = lcol_of(u0 + uu, h), kc = k < kend ? k : c - 8;
 #pragma unroll
-            for (int b = 0; b < R16; ++b) {
-                const u32x4 v = *reinterpret_cast<const u32x4*>(L + (int64_t)(b * 16 + m) * c + kc);
-                lb[u][h][b] = k < kend ? v : (u32x4){0, 0, 0, 0};     // columns past the slice contribute nothing
+                for (int b = 0; b < R16; ++b) {
+                    lb[uu][h][b] = (u32x4){0, 0, 0, 0};      // columns past the slice contribute nothing
+                    if (u0 + uu < NSTEP) {
+                        const u32x4 v = *reinterpret_cast<const u32x4*>(L + (int64_t)(b * 16 + m) * c + kc);
+                        if (k < kend) lb[uu][h][b] = v;
+                    }
+                }
             }
-        }
+    };
+    if (RESIDENT) load_l(0);
     for (int i = threadIdx.x * 4; i < c; i += 64 * kLoraWaves * 4)     // c is a multiple of 16
         *reinterpret_cast<f32x4*>(cs_copy + i) = *reinterpret_cast<const f32x4*>(cs + i);
     __syncthreads();
@@ -111,18 +122,23 @@ quant_lora_rows8_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_
     for (int grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
         const int64_t row = (int64_t)grp * 8 + (m & 7);
         const bool live = row < t;
-        load_rows(grp + gridDim.x, xn);              // the next group's rows travel while this one is worked on
+        if (RESIDENT) load_rows(grp + gridDim.x, xn);   // the next group's rows travel while this one is worked on
         f32x4 acc0[R16], acc1[R16];                  // first-half products (rows 0..7 valid), second-half (rows 8..15)
 #pragma unroll
         for (int b = 0; b < R16; ++b) acc0[b] = acc1[b] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int u = 0; u < NSTEP; ++u)
+        for (int u0 = 0; u0 < NSTEP; u0 += LSTEPS) {
+            if (!RESIDENT) load_l(u0);
 #pragma unroll
-            for (int b = 0; b < R16; ++b) {
-                const bf16x8 a = __builtin_bit_cast(bf16x8, xa[u]);
-                acc0[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, lb[u][0][b]), acc0[b], 0, 0, 0);
-                acc1[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, lb[u][1][b]), acc1[b], 0, 0, 0);
-            }
+            for (int uu = 0; uu < LSTEPS; ++uu)
+#pragma unroll
+                for (int b = 0; b < R16; ++b)
+                    if (u0 + uu < NSTEP) {
+                        const bf16x8 a = __builtin_bit_cast(bf16x8, xa[u0 + uu]);
+                        acc0[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, lb[uu][0][b]), acc0[b], 0, 0, 0);
+                        acc1[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, lb[uu][1][b]), acc1[b], 0, 0, 0);
+                    }
+        }
         // row maxima of dY * cs over this wavefront's slice
         float mx = 0.0f;
 #pragma unroll
@@ -152,34 +168,40 @@ quant_lora_rows8_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_
         // global stores to be acknowledged, once per group)
         lds_barrier();
 
+        float d = 0.0f, cc = 0.0f;
         if (live) {
             float mrow = 0.0f;
 #pragma unroll
             for (int w = 0; w < kLoraWaves; ++w) mrow = fmaxf(mrow, rmax[w][m & 7]);
-            float d, cc;
             rtn_steps(mrow, d, cc);
             if (wave == 0 && lane < 8) delta[row] = d;
-            // the codes go to this wavefront's piece of LDS, [8 rows][NSTEP * 64] ...
+        }
+        // The codes go to this wavefront's piece of LDS, [8 rows][PS * 64], and leave as 16-byte stores that cover a
+        // row's slice with consecutive lanes, so that every store instruction writes whole lines; PS steps at a time
+        // (all of them unless the slice is long: the staging area of 14 steps would not fit beside the column scales).
+        // Writes and reads of the piece come from the same wavefront, whose LDS operations execute in order.
 #pragma unroll
-            for (int u = 0; u < NSTEP; ++u) {
-                const int k = col_of(u);
-                if (k < kend) {
-                    float v[8];
-                    widen_scale(xa[u], csl, k, v);
-                    *reinterpret_cast<u32x2*>(cw + (m & 7) * (NSTEP * 64) + (k - kbeg)) = pack_codes(v, cc);
+        for (int p0 = 0; p0 < NSTEP; p0 += PS) {
+            if (live) {
+#pragma unroll
+                for (int u = p0; u < p0 + PS && u < NSTEP; ++u) {
+                    const int k = col_of(u);
+                    if (k < kend) {
+                        float v[8];
+                        widen_scale(xa[u], csl, k, v);
+                        *reinterpret_cast<u32x2*>(cw + (m & 7) * (PS * 64) + (k - kbeg - p0 * 64)) = pack_codes(v, cc);
+                    }
                 }
             }
-        }
-        // ... and leave as 16-byte stores that cover a row's whole slice (kw bytes) with consecutive lanes, so that
-        // every store instruction writes whole lines
-        {
-            const int cpr = (kend - kbeg + 15) >> 4;          // 16-byte chunks per row (slice ends are multiples of 16)
+            const int pbeg = kbeg + p0 * 64;                                      // first column of this pass
+            const int pend = pbeg + PS * 64 < kend ? pbeg + PS * 64 : kend;
+            const int cpr = pend > pbeg ? (pend - pbeg + 15) >> 4 : 0;           // 16-byte chunks per row
             for (int q = lane; q < 8 * cpr; q += 64) {
                 const int rr = q / cpr, ch = q - rr * cpr;
                 const int64_t orow = (int64_t)grp * 8 + rr;
                 if (orow < t)
-                    *reinterpret_cast<u32x4*>(Xq + orow * (int64_t)c + kbeg + ch * 16) =
-                        *reinterpret_cast<const u32x4*>(cw + rr * (NSTEP * 64) + ch * 16);
+                    *reinterpret_cast<u32x4*>(Xq + orow * (int64_t)c + pbeg + ch * 16) =
+                        *reinterpret_cast<const u32x4*>(cw + rr * (PS * 64) + ch * 16);
             }
         }
         // fixed-order sums over the eight wavefronts of each part
@@ -199,8 +221,12 @@ quant_lora_rows8_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_
             }
         }
         lds_barrier();                               // red and rmax are rewritten by the next group
+        if (RESIDENT) {
 #pragma unroll
-        for (int u = 0; u < NSTEP; ++u) xa[u] = xn[u];
+            for (int u = 0; u < NSTEP; ++u) xa[u] = xn[u];
+        } else if (grp + (int)gridDim.x < ngroups) {
+            load_rows(grp + gridDim.x, xa);
+        }
     }
 }
 
@@ -212,19 +238,25 @@ static bool launch_rows8(const uint16_t* X, int64_t t, int c, int64_t ldx, const
     // one persistent workgroup per compute unit (fewer when there are fewer 8-row groups)
     const int ngroups = (int)((t + 7) / 8);
     const dim3 grid((unsigned)(ngroups < 256 ? ngroups : 256)), block(64 * kLoraWaves);
-#define QUAFF_R8(NS)                                                                                                  \
+#define QUAFF_R8(NS, RES)                                                                                             \
     {                                                                                                                 \
-        const size_t lds = (((size_t)c * 4 + 255) & ~(size_t)255) + (size_t)kLoraWaves * 8 * NS * 64;                 \
-        auto kern = quant_lora_rows8_kernel<R16, NS>;                                                                 \
+        const size_t lds = (((size_t)c * 4 + 255) & ~(size_t)255) +                                                   \
+                           (size_t)kLoraWaves * 8 * (NS > 9 ? (NS + 1) / 2 : NS) * 64;                                \
+        auto kern = quant_lora_rows8_kernel<R16, NS, RES>;                                                            \
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,      \
                                 (int)lds) != hipSuccess)                                                              \
             return false;                                                                                             \
         hipLaunchKernelGGL(kern, grid, block, lds, stream, X, t, c, ldx, cs, Xq, delta, L, scale, T_hi, T_lo, ngroups); \
     }
-    // Longer rows stay with the two-role launch: nine steps (9216 columns) of resident L fragments and prefetched rows
-    // do not fit the 128 registers a 16-wavefront workgroup has per lane.
-    if (nstep <= 3) QUAFF_R8(3)
-    else if (nstep <= 5) QUAFF_R8(5)
+    // Longer rows: nine and more steps of resident L fragments and prefetched rows do not fit the 128 registers a
+    // 16-wavefront workgroup has per lane.  The form that fetches L again for every group then moves twice the bytes of
+    // dY through the L2 -> L1 path and is level with the two-role launch up to a few thousand rows (31 against 28 us at
+    // 2048 x 9216); with many rows it reads dY once from HBM where the two-role launch reads it twice: 16384 x 13824
+    // 306 against 341 us, 16384 x 9216 177 against 180, 8192 x 9216 87 against 90.
+    if (nstep <= 3) QUAFF_R8(3, true)
+    else if (nstep <= 5) QUAFF_R8(5, true)
+    else if (nstep <= 9 && ngroups >= 1024) QUAFF_R8(9, false)
+    else if (nstep <= 14 && ngroups >= 1024) QUAFF_R8(14, false)
     else return false;
 #undef QUAFF_R8
     return true;

@@ -43,3 +43,18 @@ def test_long_inputs(t, c_in, outliers):
         assert torch.equal(getattr(L, f), getattr(L2, f)), f
     n = len(outliers)
     assert torch.equal(L.cmax[:n], L2.cmax[:n])
+
+
+# long gradients (at least 1024 groups of 8 rows) with rows of 5136 .. 14336 columns: the backward quantizer +
+# down-projection reads dY once with L fetched per row group; both slice lengths it is instantiated for, ragged rows
+@pytest.mark.parametrize("t,c_out", [(8192 + 13, 9216), (8192 + 1, 13824), (8192 + 8, 5136)],
+                         ids=["c_out9216", "c_out13824", "c_out5136"])
+def test_long_gradients(t, c_out):
+    from tests.gpu_harness import Layer, OracleLayer, check_prepare, check_step
+    ec = synth.EdgeCase("long_grad_c%d" % c_out, t, 64, c_out, [3, 60], 16, zero_rows=[7, t - 1])
+    print("long gradient t=%d c_out=%d" % (t, c_out), flush=True)
+    sys.stdout.flush()
+    X, dY, W, O, A, B = synth.edge_case_inputs(ec, 77)
+    L, R = Layer(W, O, A, B, 1.0, t), OracleLayer(W, O, A, B, 1.0)
+    check_prepare(L, R)
+    check_step(L, R, X, dY, 0.2, tag="long gradient c_out=%d" % c_out)
