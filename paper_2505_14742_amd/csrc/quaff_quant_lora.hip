@@ -92,7 +92,10 @@ quant_lora_rows8_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_
             if (live && k < kend) dst[u] = *reinterpret_cast<const u32x4*>(xrow + k);
         }
     };
-    u32x4 xa[NSTEP], xn[NSTEP];                    // (xn costs no registers when RESIDENT is false)
+    // The next group's rows are requested ahead only where the registers allow it without spilling (three steps);
+    // with five steps the version without is 4 % faster (16384 x 5120: 75.8 against 78.8 us) and writes no scratch.
+    constexpr bool PF = RESIDENT && NSTEP <= 3;
+    u32x4 xa[NSTEP], xn[NSTEP];                    // (xn costs no registers when PF is false)
     load_rows(blockIdx.x, xa);
     constexpr int BU = NSTEP > 9 ? 2 : 3;          // RESIDENT = false: steps whose fragments of L are in flight together
     constexpr int LSTEPS = RESIDENT ? NSTEP : BU;
@@ -122,7 +125,7 @@ quant_lora_rows8_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_
     for (int grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
         const int64_t row = (int64_t)grp * 8 + (m & 7);
         const bool live = row < t;
-        if (RESIDENT) load_rows(grp + gridDim.x, xn);   // the next group's rows travel while this one is worked on
+        if (PF) load_rows(grp + gridDim.x, xn);      // the next group's rows travel while this one is worked on
         f32x4 acc0[R16], acc1[R16];                  // first-half products (rows 0..7 valid), second-half (rows 8..15)
 #pragma unroll
         for (int b = 0; b < R16; ++b) acc0[b] = acc1[b] = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -221,7 +224,7 @@ quant_lora_rows8_kernel(const uint16_t* __restrict__ X, int64_t t, int c, int64_
             }
         }
         lds_barrier();                               // red and rmax are rewritten by the next group
-        if (RESIDENT) {
+        if (PF) {
 #pragma unroll
             for (int u = 0; u < NSTEP; ++u) xa[u] = xn[u];
         } else if (grp + (int)gridDim.x < ngroups) {
